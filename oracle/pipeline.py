@@ -1,0 +1,114 @@
+"""Whole iterations of the path, assembled from the CPU checker's steps
+(test infrastructure; see gf_oracle.c for the arithmetic of each step).
+
+Order of one iteration with coarse-grained sparse communication on
+(Section 3.2 and Algorithm 1 of the paper):
+
+  acc = g + hg                       allreduce preprocess
+  l1[p][c] = ||acc_p[chunk c]||_1    local chunk norms
+  pack important chunks as fp16(acc*S); hg = 0 there, hg = momentum*acc elsewhere
+  ring allreduce of the packed buffer (Section 2.4), fp16 rounded at every hop
+  unpack: out[chunk] = fp32(reduced) / S at the important chunks
+  score, select the important chunks of the next iteration
+
+Two schedules of the selection are provided.  "lagged" is the paper's: the
+chunks used at iteration t were chosen at the end of iteration t-1 from the
+state after the allreduce (sent chunks scored by the norm of their reduced
+values, each GPU dividing by the GPU count before the norms are summed).
+Iteration 0 has no predecessor and picks from its own accumulated gradients.
+"immediate" picks, in every iteration, from that iteration's accumulated
+gradients before packing.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Callable, Dict, List, Optional, Sequence
+
+import numpy as np
+
+from . import binding as ob
+
+
+def fuse(tensors: Sequence[np.ndarray], sizes: Sequence[int]) -> np.ndarray:
+    """Place ID-ordered tensors in the pool (Section 3.1: tensor m first)."""
+    off, N = ob.layout(sizes)
+    pool = np.empty(N, dtype=np.float32)
+    for j, t in enumerate(tensors):
+        assert t.size == sizes[j]
+        pool[off[j]:off[j] + sizes[j]] = np.asarray(t, dtype=np.float32).ravel()
+    return pool
+
+
+def views(pool: np.ndarray, sizes: Sequence[int]) -> List[np.ndarray]:
+    off, _ = ob.layout(sizes)
+    return [pool[off[j]:off[j] + sizes[j]] for j in range(len(sizes))]
+
+
+def dense_iteration(pools: np.ndarray, sizes: Sequence[int], theta: int, S: float,
+                    wire: str = "f16") -> Dict[str, np.ndarray]:
+    """pools [P, N] fp32.  Lazy allreduce without sparsification: cast, one ring
+    allreduce per bucket, cast back (times 1/S)."""
+    P, N = pools.shape
+    lo, hi = ob.buckets(sizes, theta)
+    send = ob.cast_dense(pools, S, wire)
+    reduced = np.empty(N, dtype=send.dtype)
+    for a, b in zip(lo, hi):
+        reduced[a:b] = ob.ring_fold(np.ascontiguousarray(send[:, a:b]), wire)
+    out = ob.unpack_dense(reduced, np.float32(1.0) / np.float32(S), wire)
+    return dict(send=send, reduced=reduced, out=out, bucket_lo=lo, bucket_hi=hi)
+
+
+@dataclass
+class CscState:
+    hg: np.ndarray                       # [P, N] historical gradients
+    sel: Optional[np.ndarray] = None     # lagged schedule: chunks to send next
+
+
+def new_state(P: int, N: int) -> CscState:
+    return CscState(hg=np.zeros((P, N), dtype=np.float32))
+
+
+def csc_iteration(state: CscState, pools: np.ndarray, C: int, k: int, S: float, mu: float,
+                  schedule: str = "lagged", wire: str = "f16",
+                  out: Optional[np.ndarray] = None,
+                  choose: Optional[Callable[[str, np.ndarray, np.ndarray], np.ndarray]] = None
+                  ) -> Dict[str, np.ndarray]:
+    """One iteration; updates `state` in place and returns every intermediate.
+
+    choose(stage, score, sel) may replace a selection (stage is "pre" for one
+    taken before packing, "post" for one taken after the allreduce); tests use
+    it to impose an equally valid choice when scores tie within tolerance.
+    """
+    assert schedule in ("lagged", "immediate")
+    P, N = pools.shape
+    r: Dict[str, np.ndarray] = {}
+    acc = ob.accumulate(pools, state.hg)
+    l1 = ob.chunk_l1(acc, C)
+    r["acc"], r["l1"] = acc, l1
+
+    if schedule == "immediate" or state.sel is None:
+        sc = ob.score(l1)
+        sel, _ = ob.select(sc, k)
+        if choose is not None:
+            sel = choose("pre", sc, sel)
+        r["score_pre"] = sc
+    else:
+        sel = state.sel
+    r["sel"] = sel
+
+    send, hg = ob.pack_residual(acc, C, sel, S, mu, wire)
+    state.hg = hg
+    reduced = ob.ring_fold(send, wire)
+    if out is None:
+        out = np.zeros(N, dtype=np.float32)
+    red_l1 = ob.unpack(reduced, N, C, sel, np.float32(1.0) / np.float32(S), out, wire)
+    r.update(send=send, hg=hg, reduced=reduced, out=out, red_l1=red_l1)
+
+    if schedule == "lagged":
+        sc = ob.score(l1, sel, red_l1)
+        nxt, _ = ob.select(sc, k)
+        if choose is not None:
+            nxt = choose("post", sc, nxt)
+        state.sel = nxt
+        r["score_post"], r["sel_next"] = sc, nxt
+    return r

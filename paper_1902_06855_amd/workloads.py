@@ -1,0 +1,185 @@
+"""Seeded synthetic gradient sets shaped like the paper's two ImageNet models.
+
+This module only describes tensor shapes and draws random numbers.  It holds
+none of the method's arithmetic (no layout, bucketing, casting, scoring,
+selection or reduction), so both the HIP path and the CPU checker may be fed
+from it.
+
+The paper trains AlexNet and ResNet-50 on ImageNet-1K (Section 2.3, the figure
+listing per-layer parameter counts); those gradients are not available, so
+tensors of the same shapes filled with seeded normal noise stand in for them:
+for worker p and tensor l the standard deviation sigma[l, p] is drawn once,
+log-uniform in [1e-4, 1e-1], and every iteration t draws fresh N(0, sigma^2)
+values from a generator seeded by (seed, t, p, l).
+
+Tensor lists are in ID order 1..m = forward order of the network (weight before
+bias; conv weight, BN gamma, BN beta; the downsample branch after conv3; the
+classifier last).  Backward produces them in the opposite order.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+
+def tiny_sizes() -> List[int]:
+    return [4096, 16384, 65536, 131072, 262144, 524288]
+
+
+def alexnet_sizes() -> List[int]:
+    """Grouped two-tower AlexNet: 16 tensors, 60 965 224 parameters."""
+    convs = [(96, 3, 11, 11), (256, 48, 5, 5), (384, 256, 3, 3),
+             (384, 192, 3, 3), (256, 192, 3, 3)]
+    fcs = [(4096, 9216), (4096, 4096), (1000, 4096)]
+    out: List[int] = []
+    for s in convs:
+        out += [int(np.prod(s)), s[0]]
+    for s in fcs:
+        out += [s[0] * s[1], s[0]]
+    return out
+
+
+def resnet50_sizes() -> List[int]:
+    """ResNet-50 (bottleneck stages [3,4,6,3]): 161 tensors, 25 557 032 parameters."""
+    out: List[int] = [64 * 3 * 7 * 7, 64, 64]
+    inplanes = 64
+    for width, blocks in zip((64, 128, 256, 512), (3, 4, 6, 3)):
+        for b in range(blocks):
+            out += [width * inplanes, width, width]            # 1x1 reduce + BN
+            out += [width * width * 9, width, width]           # 3x3 + BN
+            out += [4 * width * width, 4 * width, 4 * width]   # 1x1 expand + BN
+            if b == 0:                                         # projection shortcut
+                out += [4 * width * inplanes, 4 * width, 4 * width]
+            inplanes = 4 * width
+    out += [1000 * 2048, 1000]
+    return out
+
+
+@dataclass
+class Workload:
+    """One benchmark / parity configuration (shapes and scalars only)."""
+    name: str
+    sizes: List[int]               # tensor element counts, ID order 1..m
+    P: int                         # simulated workers
+    chunk: int                     # chunk elements, 0 = dense path
+    density: float                 # fraction of chunks selected (CSC only)
+    loss_scale: float
+    theta: int                     # fusion threshold in wire elements
+    iterations: int = 1
+    mu: float = 1.0
+    seed: int = 1902_06855
+    wire: str = "f16"
+    extra: dict = field(default_factory=dict)
+
+    @property
+    def m(self) -> int:
+        return len(self.sizes)
+
+    @property
+    def N(self) -> int:
+        return int(sum(self.sizes))
+
+    def k_for(self, n_chunks: int) -> int:
+        """Selected-chunk count for this density: ceil(density * n_chunks) in [1, n_chunks]."""
+        return max(1, min(n_chunks, math.ceil(self.density * n_chunks - 1e-9)))
+
+
+MB = 1 << 20
+
+
+def config(name: str) -> Workload:
+    """The five configurations this build is measured and checked on."""
+    if name == "tiny":
+        return Workload("tiny", tiny_sizes(), P=4, chunk=4096, density=0.25,
+                        loss_scale=1024.0, theta=1 << 40)
+    if name == "alexnet_dense":
+        return Workload("alexnet_dense", alexnet_sizes(), P=8, chunk=0, density=1.0,
+                        loss_scale=1024.0, theta=32 * MB // 2)
+    if name == "resnet50_dense_4mb":
+        return Workload("resnet50_dense_4mb", resnet50_sizes(), P=8, chunk=0, density=1.0,
+                        loss_scale=128.0, theta=4 * MB // 2)
+    if name == "resnet50_dense_64mb":
+        return Workload("resnet50_dense_64mb", resnet50_sizes(), P=8, chunk=0, density=1.0,
+                        loss_scale=128.0, theta=64 * MB // 2)
+    if name == "alexnet_csc":
+        return Workload("alexnet_csc", alexnet_sizes(), P=16, chunk=32768, density=0.10,
+                        loss_scale=1024.0, theta=1 << 40, iterations=10)
+    if name == "resnet50_csc":
+        return Workload("resnet50_csc", resnet50_sizes(), P=64, chunk=8192, density=0.01,
+                        loss_scale=128.0, theta=1 << 40, iterations=20)
+    raise KeyError(name)
+
+
+CONFIG_NAMES = ("tiny", "alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb",
+                "alexnet_csc", "resnet50_csc")
+
+
+def scaled(w: Workload, divisor: int, name: Optional[str] = None) -> Workload:
+    """A copy of `w` whose tensors are `divisor` times smaller (each at least 8,
+    rounded to a multiple of 8) with chunk and theta shrunk alike; keeps the
+    tensor count and the size mix."""
+    sizes = [max(8, (s // divisor) // 8 * 8) for s in w.sizes]
+    chunk = 0 if w.chunk == 0 else max(64, w.chunk // divisor)
+    theta = w.theta if w.theta >= (1 << 40) else max(1, w.theta // divisor)
+    return Workload(name or f"{w.name}_div{divisor}", sizes, w.P, chunk, w.density,
+                    w.loss_scale, theta, w.iterations, w.mu, w.seed, w.wire, dict(w.extra))
+
+
+def _mix(*vals: int) -> int:
+    """Deterministic 63-bit hash of a tuple of small integers (splitmix-style)."""
+    x = 0x9E3779B97F4A7C15
+    for v in vals:
+        x ^= (int(v) + 0x9E3779B97F4A7C15) & 0xFFFFFFFFFFFFFFFF
+        x = (x * 0xBF58476D1CE4E5B9) & 0xFFFFFFFFFFFFFFFF
+        x ^= x >> 31
+        x = (x * 0x94D049BB133111EB) & 0xFFFFFFFFFFFFFFFF
+        x ^= x >> 29
+    return x & 0x7FFFFFFFFFFFFFFF
+
+
+def sigma_table(w: Workload) -> np.ndarray:
+    """sigma[l, p], log-uniform in [1e-4, 1e-1], fixed for the whole run."""
+    rng = np.random.default_rng(_mix(w.seed, 0xA11CE))
+    e = rng.uniform(-4.0, -1.0, size=(w.m, w.P))
+    return (10.0 ** e).astype(np.float32)
+
+
+def gradient_tensor(w: Workload, sig: np.ndarray, t: int, p: int, l: int,
+                    device: str = "cpu") -> torch.Tensor:
+    """Tensor l (0-based ID-order index) of worker p at iteration t, fp32."""
+    g = torch.Generator(device=device)
+    g.manual_seed(_mix(w.seed, t, p, l))
+    x = torch.randn(w.sizes[l], generator=g, device=device, dtype=torch.float32)
+    return x.mul_(float(sig[l, p]))
+
+
+def gradients(w: Workload, t: int, device: str = "cpu",
+              sig: Optional[np.ndarray] = None) -> List[List[torch.Tensor]]:
+    """grads[p][l]: separately allocated tensors, ID order, for iteration t.
+
+    The values depend on `device` (torch's CPU and GPU generators differ); a
+    caller that needs the same bits on both sides generates once and copies.
+    """
+    if sig is None:
+        sig = sigma_table(w)
+    return [[gradient_tensor(w, sig, t, p, l, device) for l in range(w.m)]
+            for p in range(w.P)]
+
+
+def integer_gradients(sizes: Sequence[int], P: int, seed: int, lo: int = -8, hi: int = 8
+                      ) -> List[List[torch.Tensor]]:
+    """Small-integer-valued fp32 tensors: every partial sum is exactly
+    representable, which makes sums independent of their order."""
+    out = []
+    for p in range(P):
+        row = []
+        for l, n in enumerate(sizes):
+            g = torch.Generator()
+            g.manual_seed(_mix(seed, p, l, 77))
+            row.append(torch.randint(lo, hi + 1, (n,), generator=g).to(torch.float32))
+        out.append(row)
+    return out

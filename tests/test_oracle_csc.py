@@ -1,0 +1,226 @@
+"""Pins for the CPU checker's coarse-grained sparse communication steps
+(Section 3.2, Algorithm 1) and for whole iterations."""
+import numpy as np
+import pytest
+
+from oracle import binding as ob, pipeline as op
+from paper_1902_06855_amd import workloads as wl
+
+
+def _pools(w, t, integer=False):
+    if integer:
+        g = wl.integer_gradients(w.sizes, w.P, seed=w.seed + t)
+    else:
+        g = wl.gradients(w, t)
+    return np.stack([op.fuse([x.numpy() for x in row], w.sizes) for row in g])
+
+
+def small(P=3, C=96, density=0.3, sizes=(50, 8, 700, 33, 1200, 64, 5)):
+    return wl.Workload("small", list(sizes), P=P, chunk=C, density=density, loss_scale=64.0,
+                       theta=1 << 40)
+
+
+# ------------------------------------------------------------------ chunk L1
+
+def test_chunk_l1_brute_force_and_short_last_chunk():
+    rng = np.random.default_rng(0)
+    N, C = 10_007, 256
+    x = (rng.standard_normal(N) * 1e-3).astype(np.float32)
+    got = ob.chunk_l1_f64(x, C)
+    assert got.size == 40
+    for c in range(40):
+        seg = x[c * C:(c + 1) * C].astype(np.float64)
+        assert got[c] == pytest.approx(np.abs(seg).sum(), rel=1e-13)
+    assert got[-1] == pytest.approx(np.abs(x[39 * C:].astype(np.float64)).sum(), rel=1e-13)
+    # exact on integers, sign ignored
+    y = np.arange(-50, 50, dtype=np.float32)
+    assert list(ob.chunk_l1_f64(y, 25)) == [sum(abs(v) for v in range(-50 + 25 * c, -25 + 25 * c))
+                                            for c in range(4)]
+
+
+def test_triangle_inequality_between_summed_and_local_norms():
+    w = small()
+    pools = _pools(w, 0)
+    l1 = ob.chunk_l1(pools, w.chunk)
+    total = pools.astype(np.float64).sum(axis=0).astype(np.float32)
+    l1_of_sum = ob.chunk_l1_f64(total, w.chunk)
+    assert np.all(l1_of_sum <= l1.astype(np.float64).sum(axis=0) * (1 + 1e-6))
+
+
+# --------------------------------------------------------------------- score
+
+def test_score_without_sent_chunks_is_the_sum_over_workers():
+    rng = np.random.default_rng(1)
+    l1 = rng.random((5, 40)).astype(np.float32)
+    sc = ob.score(l1)
+    assert np.array_equal(sc, l1.astype(np.float64).sum(axis=0).astype(np.float32))
+
+
+def test_score_of_sent_chunks_is_the_norm_of_the_reduced_values():
+    # every GPU holds the same reduced chunk and divides its norm by the GPU
+    # count, so the sum over GPUs gives that norm back
+    rng = np.random.default_rng(2)
+    P, nc = 8, 30
+    l1 = rng.random((P, nc)).astype(np.float32)
+    sent = np.array([3, 4, 17], dtype=np.int32)
+    red = np.array([10.0, 0.25, 7.5], dtype=np.float32)
+    sc = ob.score(l1, sent, red)
+    base = ob.score(l1)
+    keep = np.setdiff1d(np.arange(nc), sent)
+    assert np.array_equal(sc[keep], base[keep])
+    assert np.allclose(sc[sent], red, rtol=1e-6) and np.array_equal(sc[sent], red)  # P = 8 divides exactly
+    # with one GPU the two rules coincide
+    l1_one = rng.random((1, nc)).astype(np.float32)
+    assert np.array_equal(ob.score(l1_one, sent, l1_one[0, sent]), ob.score(l1_one))
+    # a GPU count that is not a power of two still returns the norm to rounding
+    sc3 = ob.score(l1[:3].copy(), sent, red)
+    assert np.allclose(sc3[sent], red, rtol=2e-7)
+
+
+# ----------------------------------------------------------------- selection
+
+def _select_by_full_sort(score, k):
+    order = sorted(range(len(score)), key=lambda c: (-float(score[c]), c))
+    return np.array(sorted(order[:k]), dtype=np.int32)
+
+
+def test_select_equals_a_full_sort():
+    rng = np.random.default_rng(3)
+    for n in (1, 2, 17, 245, 3120):
+        sc = rng.random(n).astype(np.float32)
+        sc[rng.integers(0, n, size=n // 3)] = sc[0]          # plenty of exact ties
+        for k in {1, max(1, n // 10), max(1, n // 2), n}:
+            sel, mask = ob.select(sc, k)
+            assert np.array_equal(sel, _select_by_full_sort(sc, k))
+            assert mask.sum() == k and np.all(mask[sel] == 1)
+            assert np.all(np.diff(sel) > 0)
+
+
+def test_select_special_cases():
+    sc = np.array([0.5, 3.0, 3.0, 0.1, 2.0], dtype=np.float32)
+    assert list(ob.select(sc, 1)[0]) == [1]                  # argmax, lower index on a tie
+    assert list(ob.select(sc, 2)[0]) == [1, 2]
+    assert list(ob.select(sc, 3)[0]) == [1, 2, 4]
+    assert list(ob.select(sc, 5)[0]) == [0, 1, 2, 3, 4]
+    z = np.zeros(9, dtype=np.float32)
+    assert list(ob.select(z, 4)[0]) == [0, 1, 2, 3]          # all tied -> lowest indices
+
+
+# ------------------------------------------------- pack + historical gradient
+
+@pytest.mark.parametrize("mu", [1.0, 0.9])
+def test_each_element_is_either_sent_or_kept(mu):
+    w = small()
+    pools = _pools(w, 0)
+    hg0 = (_pools(w, 1) * 0.5).astype(np.float32)
+    acc = ob.accumulate(pools, hg0)
+    assert np.array_equal(acc, pools + hg0)
+    nc = ob.n_chunks(w.N, w.chunk)
+    sel = np.array([0, 2, 5, nc - 1], dtype=np.int32)        # includes the short last chunk
+    send, hg = ob.pack_residual(acc, w.chunk, sel, w.loss_scale, mu)
+    L = ob.packed_len(w.N, w.chunk, sel)
+    assert send.shape == (w.P, L) and L == 3 * w.chunk + (w.N - (nc - 1) * w.chunk)
+    slot = 0
+    sent_mask = np.zeros(w.N, dtype=bool)
+    for c in sel:
+        lo, hi = c * w.chunk, min(w.N, (c + 1) * w.chunk)
+        sent_mask[lo:hi] = True
+        want = (acc[:, lo:hi] * np.float32(w.loss_scale)).astype(np.float16).view(np.uint16)
+        assert np.array_equal(send[:, slot:slot + hi - lo], want)
+        slot += hi - lo
+    assert slot == L
+    assert np.all(hg[:, sent_mask] == 0) and not np.signbit(hg[:, sent_mask]).any()
+    assert np.array_equal(hg[:, ~sent_mask], (np.float32(mu) * acc[:, ~sent_mask]).astype(np.float32))
+    if mu == 1.0:                                            # nothing is lost, nothing is doubled
+        back = ob.f16_to_f32(send) / np.float32(w.loss_scale)
+        assert np.allclose(back, acc[:, sent_mask], rtol=2 ** -10, atol=2.0 ** -24 / w.loss_scale)
+
+
+# ------------------------------------------------------------ whole iterations
+
+@pytest.mark.parametrize("schedule", ["immediate", "lagged"])
+def test_no_gradient_is_lost_over_iterations(schedule):
+    """Algorithm 1 with momentum 1: what was sent plus what is still held back
+    equals everything ever computed (the paper: CSC loses no learned
+    information).  Small integers, loss scale 1: every sum is exact."""
+    w = small(P=4, C=64, density=0.2)
+    nc = ob.n_chunks(w.N, w.chunk)
+    k = w.k_for(nc)
+    st = op.new_state(w.P, w.N)
+    total_in = np.zeros(w.N, dtype=np.float64)
+    total_out = np.zeros(w.N, dtype=np.float64)
+    for t in range(7):
+        pools = _pools(w, t, integer=True)
+        total_in += pools.astype(np.float64).sum(axis=0)
+        out = np.zeros(w.N, dtype=np.float32)
+        r = op.csc_iteration(st, pools, w.chunk, k, 1.0, 1.0, schedule, out=out)
+        total_out += out
+        assert len(r["sel"]) == k
+        held = st.hg.astype(np.float64).sum(axis=0)
+        assert np.array_equal(total_out + held, total_in)
+    assert np.abs(total_out).sum() > 0 and np.abs(held).sum() > 0
+
+
+def test_lagged_schedule_uses_the_previous_iterations_choice():
+    w = small(P=3, C=128, density=0.25)
+    nc = ob.n_chunks(w.N, w.chunk)
+    k = w.k_for(nc)
+    st = op.new_state(w.P, w.N)
+    prev_next = None
+    for t in range(4):
+        r = op.csc_iteration(st, _pools(w, t), w.chunk, k, w.loss_scale, 1.0, "lagged")
+        if t == 0:
+            assert "score_pre" in r                         # bootstrap from own gradients
+            assert np.array_equal(r["sel"], ob.select(ob.score(r["l1"]), k)[0])
+        else:
+            assert "score_pre" not in r and np.array_equal(r["sel"], prev_next)
+        # next choice: sent chunks scored by the reduced norm, others by the summed local norms
+        sc = r["score_post"]
+        assert np.allclose(sc[r["sel"]], r["red_l1"], rtol=1e-6)
+        rest = np.setdiff1d(np.arange(nc), r["sel"])
+        assert np.array_equal(sc[rest], ob.score(r["l1"])[rest])
+        prev_next = r["sel_next"]
+
+
+def test_sending_every_chunk_equals_the_dense_path():
+    w = small(P=4, C=100, density=1.0)
+    nc = ob.n_chunks(w.N, w.chunk)
+    st = op.new_state(w.P, w.N)
+    for t in range(2):
+        pools = _pools(w, t)
+        r = op.csc_iteration(st, pools, w.chunk, nc, w.loss_scale, 1.0, "immediate")
+        d = op.dense_iteration(pools, w.sizes, 1 << 40, w.loss_scale)
+        assert np.all(st.hg == 0)
+        assert np.array_equal(r["send"], d["send"])
+        assert np.array_equal(r["reduced"], d["reduced"])
+        assert np.array_equal(r["out"], d["out"])
+
+
+def test_dense_iteration_reduces_each_bucket_on_its_own_ring():
+    w = wl.Workload("d", [40, 24, 200, 8, 120], P=3, chunk=0, density=1.0, loss_scale=8.0, theta=100)
+    pools = _pools(w, 0)
+    d = op.dense_iteration(pools, w.sizes, w.theta, w.loss_scale)
+    lo, hi = d["bucket_lo"], d["bucket_hi"]
+    assert len(lo) > 1
+    for a, b in zip(lo, hi):
+        assert np.array_equal(d["reduced"][a:b], ob.ring_fold(np.ascontiguousarray(d["send"][:, a:b])))
+    # dense result is close to the fp64 sum (fp16 relative error per hop)
+    exact = pools.astype(np.float64).sum(axis=0)
+    scale = np.abs(pools.astype(np.float64)).sum(axis=0)
+    assert np.all(np.abs(d["out"] - exact) <= scale * 3 * 2.0 ** -10 + 1e-7)
+
+
+def test_unselected_positions_of_the_output_are_not_written():
+    w = small()
+    nc = ob.n_chunks(w.N, w.chunk)
+    st = op.new_state(w.P, w.N)
+    out = np.full(w.N, np.float32(-123.0))
+    r = op.csc_iteration(st, _pools(w, 0), w.chunk, 3, w.loss_scale, 1.0, "immediate", out=out)
+    m = np.zeros(w.N, dtype=bool)
+    for c in r["sel"]:
+        m[c * w.chunk:(c + 1) * w.chunk] = True
+    assert np.all(out[~m] == -123.0) and np.all(out[m] != -123.0)
+    # reduced norms are norms of what was written
+    for j, c in enumerate(r["sel"]):
+        seg = out[c * w.chunk:min(w.N, (c + 1) * w.chunk)].astype(np.float64)
+        assert r["red_l1"][j] == pytest.approx(np.abs(seg).sum(), rel=1e-6)
