@@ -1,0 +1,210 @@
+/*
+ * gf.h -- C ABI of the MI355X (gfx950) implementation of one worker's
+ * gradient-aggregation path of GradientFlow (arxiv 1902.06855).
+ *
+ * Notation (the paper's): m gradient tensors with IDs 1..m, produced by the
+ * backward pass in the order m..1; N = total elements; P = number of workers
+ * ("GPUs" in the paper; here P buffers resident in one GPU's memory); theta =
+ * lazy-allreduce threshold; C = gradients per chunk; k = number of important
+ * chunks; S = loss scale; hg = historical gradient (Algorithm 1).
+ *
+ * Conventions for every call
+ *   - "device" pointers are HIP device memory owned by the caller; "host"
+ *     pointers are ordinary host memory.  Pointer *tables* (arrays of
+ *     pointers) passed to the compute calls are themselves device arrays.
+ *   - The library owns only the plan (host tables + a few KB of device
+ *     tables).  Compute calls allocate nothing, never synchronise with the
+ *     host, and are enqueued on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream).
+ *   - Data pointers need only their natural alignment (4 bytes for fp32,
+ *     2 bytes for fp16); 16-byte aligned tensors take the 128-bit path.
+ *   - Errors are return codes; nothing throws.  Arguments are validated on
+ *     the host before anything is launched.  Non-finite inputs are not
+ *     detected: infinities and NaNs propagate by IEEE rules.
+ *   - fp16 means IEEE binary16; every fp32->fp16 conversion rounds to nearest
+ *     even, keeps subnormals and overflows to infinity.
+ *   - A call's outputs must not overlap its inputs unless stated.
+ */
+#ifndef GF_H
+#define GF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GF_OK = 0,
+    GF_EINVAL = 1,   /* bad argument (null where required, out of range, wrong mode) */
+    GF_ENOMEM = 2,   /* host or device allocation failed (plan calls only)          */
+    GF_EHIP = 3,     /* a HIP runtime call or kernel launch failed                  */
+    GF_ESTATE = 4    /* plan has no device tables yet (call gf_plan_to_device)      */
+} gf_status;
+
+/* Element type of what travels between workers (Section 2.5: fp16 gradients go
+ * into allreduce under mixed precision; Section 2.3: fp32 in the baseline). */
+typedef enum { GF_WIRE_F16 = 0, GF_WIRE_F32 = 1 } gf_wire;
+
+typedef struct gf_plan gf_plan;
+typedef void *gf_stream;             /* hipStream_t */
+
+/* phase bits of gf_fuse_pack */
+#define GF_PHASE_ACCUM 1u            /* g + hg, chunk norms                        */
+#define GF_PHASE_PACK  2u            /* cast, scale, pack, historical-gradient rule */
+
+const char *gf_status_string(gf_status s);
+
+/* ------------------------------------------------------------------ planning
+ * Section 3.1 (lazy allreduce) and Section 3.2 (chunk partition), host only:
+ *   - pool layout: tensor j occupies [sum_{i>j} numel_i, sum_{i>=j} numel_i);
+ *   - buckets: walking j = m..1, a bucket closes after the tensor that makes
+ *     the waited size strictly greater than theta_elems; the rest is flushed
+ *     after tensor 1; buckets hold whole tensors only;
+ *   - chunks: chunk c = pool [c*C, min(N,(c+1)*C)), n_chunks = ceil(N/C).
+ * tensor_numel: host array [m], ID order 1..m, every entry >= 1.
+ * theta_elems >= 0 in wire elements.  chunk_elems = 0 makes a dense-only plan
+ * (no sparsification; compute calls then work on internal fixed-size tiles and
+ * the ring is run per bucket); chunk_elems >= 1 makes a CSC plan (the packed
+ * buffer is reduced as one ring).  1 <= P <= 4096.
+ * gf_plan_create touches no GPU.  Returns GF_EINVAL / GF_ENOMEM on failure and
+ * leaves *out NULL. */
+gf_status gf_plan_create(gf_plan **out, const int64_t *tensor_numel, int32_t m,
+                         int64_t theta_elems, int32_t chunk_elems, int32_t P, gf_wire wire);
+
+/* Copies the plan's tables to the current HIP device (allocates; synchronous).
+ * Required once before any compute call; idempotent. */
+gf_status gf_plan_to_device(gf_plan *plan);
+
+/* Frees host and device tables.  NULL is allowed. */
+void gf_plan_destroy(gf_plan *plan);
+
+/* Any output pointer may be NULL.  n_chunks is 0 for a dense-only plan. */
+gf_status gf_plan_info(const gf_plan *plan, int64_t *N, int32_t *n_chunks, int32_t *n_buckets);
+
+/* Host copies of the layout: tensor_off [m] (ID order), bucket_lo/hi [n_buckets]
+ * (pool element ranges, generation order).  Any pointer may be NULL. */
+gf_status gf_plan_layout(const gf_plan *plan, int64_t *tensor_off, int64_t *bucket_lo,
+                         int64_t *bucket_hi);
+
+/* Ring segment length (elements) for a message of L elements: the L elements
+ * are cut into P equal segments (Section 2.4) of roundup(ceil(L/P), 16 bytes)
+ * elements; trailing segments may be short or empty.  Returns -1 on bad input. */
+int64_t gf_plan_ring_segment(const gf_plan *plan, int64_t L);
+
+/* Number of work tiles (= n_chunks for a CSC plan) and the pieces of tensors
+ * that make up tile `tile`, in pool order: piece i is `len[i]` elements of
+ * tensor `tensor[i]` (0-based ID index) starting at element `src_off[i]` of
+ * that tensor.  Returns the piece count (pieces beyond `cap` are not written),
+ * or -1 on bad input.  For tests of the fusion tables. */
+int32_t gf_plan_tiles(const gf_plan *plan);
+int32_t gf_plan_tile_pieces(const gf_plan *plan, int32_t tile, int32_t cap,
+                            int32_t *tensor, int64_t *src_off, int32_t *len);
+
+/* Bytes of device scratch the compute calls need (pass it as `workspace`,
+ * 256-byte aligned; its contents carry nothing between calls). */
+size_t gf_plan_workspace_bytes(const gf_plan *plan);
+
+/* --------------------------------------------------------------- gf_fuse_pack
+ * Lazy-allreduce fusion (Section 3.1), the allreduce-preprocess step of
+ * Algorithm 1, the local chunk norms of Section 3.2, and the cast / pack of
+ * Sections 2.5 and 3.2, for all P workers in one pass.
+ *
+ * Gradients come either as `grads`, a device table [P*m] of device pointers
+ * (entry p*m + j = worker p's tensor with 0-based ID index j, numel_j fp32
+ * values, anywhere in memory: the fusion is folded into the read), or as
+ * `pools`, a device table [P] of N-element fp32 pools already laid out as
+ * above (the paper's zero-copy design).  Exactly one of the two is non-NULL
+ * when GF_PHASE_ACCUM is set; both are ignored otherwise.
+ *
+ * residual: device table [P] of N-element fp32 historical-gradient pools,
+ *   read and written in place; NULL = dense path (acc = g, phase must be
+ *   ACCUM|PACK, sel_idx must be NULL).
+ * sel_idx:  device array [k], ascending chunk indices of the important
+ *   chunks; NULL = every chunk (k ignored).  Requires a CSC plan.
+ * sendbuf:  device table [P] of wire-typed buffers.  The j-th selected chunk
+ *   is written at element j*C (chunks in ascending order, the short last chunk
+ *   of the pool, if selected, comes last and is written at its real length);
+ *   with sel_idx NULL the buffer is the whole pool, N elements.
+ * chunk_l1: device [P*n_chunks] fp32 out (worker-major), or NULL; written
+ *   when GF_PHASE_ACCUM is set: sum of |acc| over the chunk's real elements,
+ *   accumulated in fp64, rounded once to fp32.  CSC plans only.
+ *
+ * phase = ACCUM          acc = g + hg (fp32), hg <- acc, norms out.
+ * phase = PACK           acc = hg as left by ACCUM.  Selected chunks:
+ *                        send = wire(acc * S), hg <- +0.  Others: hg <- mu*acc.
+ * phase = ACCUM | PACK   both in a single pass over the data (sel_idx is
+ *                        already known: the paper's schedule, or the dense path).
+ * mu is Algorithm 1's "momentum" applied to the historical gradient. */
+gf_status gf_fuse_pack(const gf_plan *plan, uint32_t phase,
+                       const void *const *grads, const float *const *pools,
+                       float *const *residual,
+                       const int32_t *sel_idx, int32_t k,
+                       float loss_scale, float mu,
+                       void *const *sendbuf, float *chunk_l1,
+                       void *workspace, gf_stream stream);
+
+/* ------------------------------------------------------ gf_chunk_score_select
+ * Section 3.2, important-chunk selection.  What the paper does with a small
+ * allreduce of the norm vector is here a sum over the P rows of chunk_l1.
+ *
+ * score[c] = sum_p chunk_l1[p][c]  (p ascending, fp64, rounded to fp32) for a
+ * chunk that was not sent this iteration; for prev_sel[j] (the chunks that went
+ * through this iteration's allreduce) score = sum_p (reduced_l1[j] / P): every
+ * GPU holds the same reduced values and divides its norm by the GPU count.
+ * prev_sel NULL (k_prev ignored) scores every chunk by the first rule.
+ * The k chunks with the largest score are chosen, equal scores going to the
+ * lower chunk index.
+ *
+ * chunk_l1 [P*n_chunks], reduced_l1 [k_prev], prev_sel [k_prev] ascending:
+ *   device, in.   scores [n_chunks] fp32, sel_idx [k] int32 ascending,
+ *   mask [n_chunks] bytes (1 = chosen), packed_len [1] int64 (number of
+ *   elements the chosen chunks hold): device, out; scores, mask and
+ *   packed_len may be NULL.  sel_idx may be the same buffer as prev_sel.
+ * 1 <= k <= n_chunks.  CSC plans only. */
+gf_status gf_chunk_score_select(const gf_plan *plan, const float *chunk_l1,
+                                const float *reduced_l1, const int32_t *prev_sel, int32_t k_prev,
+                                int32_t k, float *scores, int32_t *sel_idx, uint8_t *mask,
+                                int64_t *packed_len, void *workspace, gf_stream stream);
+
+/* --------------------------------------------------------- gf_ring_reduce_sim
+ * The arithmetic of ring allreduce (Section 2.4) over P send buffers that all
+ * live in this GPU's memory.  Element i of segment s ends up as the left fold
+ *     x_s[i] + x_{s+1}[i] + ... + x_{s-1}[i]      (worker indices mod P)
+ * rounded to the wire type after every addition, which is what P-1
+ * reduce-scatter hops produce when rank r first sends its segment r to rank
+ * r+1; the all-gather hops are copies.
+ *
+ * sendbuf: device table [P] of wire-typed buffers of L elements.
+ * CSC plan: one ring over [0, L).  If L_dev is non-NULL it points to a device
+ *   int64 holding the actual length (0 <= *L_dev <= L) and L only sizes the
+ *   launch; this lets the length come straight from gf_chunk_score_select.
+ * Dense plan: L must be N, L_dev NULL; every lazy-allreduce bucket is reduced
+ *   as a ring of its own (its own segments), all in one launch.
+ * reduced: device, L wire elements out.  allgather_out: NULL, or a device
+ *   table [P] of buffers that each also receive the L reduced elements. */
+gf_status gf_ring_reduce_sim(const gf_plan *plan, const void *const *sendbuf, int64_t L,
+                             const int64_t *L_dev, void *reduced, void *const *allgather_out,
+                             void *workspace, gf_stream stream);
+
+/* ------------------------------------------------------------ gf_unpack_apply
+ * Second cast of Section 2.5 and the write-back of Section 3.2:
+ *     out[c*C + i] = fp32(reduced[j*C + i]) * alpha     for c = sel_idx[j]
+ * (alpha = 1/S gives back summed gradients in unscaled units).  Positions of
+ * chunks that were not sent are not written.  sel_idx NULL = all N elements.
+ * out_pool: device N-element fp32 pool, or NULL.  out_tensors: NULL, or a
+ *   device table [m] of per-tensor fp32 destinations (0-based ID index); at
+ *   least one of the two must be given, both may be.
+ * reduced_l1: NULL, or device [k] fp32 out: sum of |out| over the j-th
+ *   selected chunk (fp64 accumulation, one rounding); needs sel_idx.
+ * L: elements in `reduced` (CSC: (k-1)*C < L <= k*C; dense: N). */
+gf_status gf_unpack_apply(const gf_plan *plan, const void *reduced, int64_t L,
+                          const int32_t *sel_idx, int32_t k, float alpha,
+                          float *out_pool, void *const *out_tensors,
+                          float *reduced_l1, void *workspace, gf_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GF_H */

@@ -1,0 +1,136 @@
+// Device-side helpers for the gfx950 kernels: wire-type conversion, 128-bit
+// accesses, deterministic wave/workgroup reductions and scans.
+#ifndef GF_DEVICE_H
+#define GF_DEVICE_H
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "gf_internal.h"
+
+// ---- global address space ---------------------------------------------------
+// Data pointers reach the kernels through pointer tables, so the compiler sees
+// generic (flat) addresses.  Everything they point to is device global memory;
+// saying so selects global_load / global_store instead of flat accesses.
+#define GF_GLOBAL __attribute__((address_space(1)))
+
+template <typename T>
+__device__ __forceinline__ GF_GLOBAL T *gf_global(T *p)
+{
+    return (GF_GLOBAL T *)p;
+}
+
+// Plain clang vector types (HIP's float4 / uint4 classes cannot live behind an
+// address-space qualified pointer).
+typedef float gf_f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t gf_u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t gf_u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- fp16 wire values travel as raw 16-bit patterns -------------------------
+// The conversions below compile to the hardware's cvt instructions, which round
+// to nearest even and keep subnormals under the default float mode of HIP
+// kernels (no flush-to-zero is requested anywhere in this library).
+
+__device__ __forceinline__ uint16_t gf_f32_to_h(float x)
+{
+    const _Float16 h = static_cast<_Float16>(x);
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ float gf_h_to_f32(uint16_t b)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, b));
+}
+
+// One ring hop on a pair of halves packed in a 32-bit word: fp32 sum rounded
+// back to half (Section 2.5: the message is fp16, so every partial sum is).
+__device__ __forceinline__ uint32_t gf_hop_add_h2(uint32_t a, uint32_t b)
+{
+    const float s0 = gf_h_to_f32(static_cast<uint16_t>(a)) + gf_h_to_f32(static_cast<uint16_t>(b));
+    const float s1 = gf_h_to_f32(static_cast<uint16_t>(a >> 16)) + gf_h_to_f32(static_cast<uint16_t>(b >> 16));
+    return static_cast<uint32_t>(gf_f32_to_h(s0)) | (static_cast<uint32_t>(gf_f32_to_h(s1)) << 16);
+}
+
+__device__ __forceinline__ uint16_t gf_hop_add(uint16_t a, uint16_t b)
+{
+    return gf_f32_to_h(gf_h_to_f32(a) + gf_h_to_f32(b));
+}
+
+__device__ __forceinline__ float gf_hop_add(float a, float b) { return a + b; }
+
+// Wire element from an fp32 value.
+template <typename W> __device__ __forceinline__ W gf_to_wire(float x);
+template <> __device__ __forceinline__ uint16_t gf_to_wire<uint16_t>(float x) { return gf_f32_to_h(x); }
+template <> __device__ __forceinline__ float gf_to_wire<float>(float x) { return x; }
+
+template <typename W> __device__ __forceinline__ float gf_from_wire(W x);
+template <> __device__ __forceinline__ float gf_from_wire<uint16_t>(uint16_t x) { return gf_h_to_f32(x); }
+template <> __device__ __forceinline__ float gf_from_wire<float>(float x) { return x; }
+
+// Four wire elements as one naturally aligned vector.
+template <typename W> struct gf_wire4;
+template <> struct gf_wire4<uint16_t> { using type = gf_u32x2; };
+template <> struct gf_wire4<float> { using type = gf_f32x4; };
+
+__device__ __forceinline__ gf_u32x2 gf_pack4(uint16_t a, uint16_t b, uint16_t c, uint16_t d)
+{
+    gf_u32x2 r;
+    r.x = static_cast<uint32_t>(a) | (static_cast<uint32_t>(b) << 16);
+    r.y = static_cast<uint32_t>(c) | (static_cast<uint32_t>(d) << 16);
+    return r;
+}
+__device__ __forceinline__ gf_f32x4 gf_pack4(float a, float b, float c, float d)
+{
+    gf_f32x4 r = {a, b, c, d};
+    return r;
+}
+
+__device__ __forceinline__ void gf_unpack4(gf_u32x2 v, float &a, float &b, float &c, float &d)
+{
+    a = gf_h_to_f32(static_cast<uint16_t>(v.x)); b = gf_h_to_f32(static_cast<uint16_t>(v.x >> 16));
+    c = gf_h_to_f32(static_cast<uint16_t>(v.y)); d = gf_h_to_f32(static_cast<uint16_t>(v.y >> 16));
+}
+__device__ __forceinline__ void gf_unpack4(gf_f32x4 v, float &a, float &b, float &c, float &d)
+{
+    a = v.x; b = v.y; c = v.z; d = v.w;
+}
+
+__device__ __forceinline__ bool gf_aligned(const void *p, unsigned bytes)
+{
+    return (reinterpret_cast<uintptr_t>(p) & (bytes - 1u)) == 0;
+}
+__device__ __forceinline__ bool gf_aligned(const GF_GLOBAL void *p, unsigned bytes)
+{
+    return (reinterpret_cast<uintptr_t>(p) & (bytes - 1u)) == 0;
+}
+
+// ---- reductions -------------------------------------------------------------
+// Fixed trees: the result depends only on the values, never on scheduling.
+
+__device__ __forceinline__ double gf_wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;   // complete in lane 0
+}
+
+// Sum over a workgroup of NT threads (NT a multiple of 64); valid in thread 0.
+template <int NT>
+__device__ __forceinline__ double gf_block_sum(double v)
+{
+    __shared__ double part[NT / 64];
+    v = gf_wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) part[wave] = v;
+    __syncthreads();
+    double s = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) s += part[w];
+    }
+    __syncthreads();
+    return s;
+}
+
+#endif  // GF_DEVICE_H

@@ -1,0 +1,262 @@
+// gf_fuse_pack: lazy-allreduce fusion folded into the read (Section 3.1), the
+// allreduce-preprocess step of Algorithm 1 (g + hg, then hg = 0 or
+// momentum * g), per-chunk L1 norms (Section 3.2) and the fp32 -> wire cast
+// with loss scaling (Section 2.5), as one HBM-streaming pass per worker tile.
+//
+// One workgroup handles one (worker, tile) pair; a tile is a chunk of a CSC
+// plan or a fixed slice of the pool of a dense plan.  Whether the tile is sent
+// is uniform across the workgroup, so each case runs its own straight-line
+// inner loop of 128-bit loads and stores with several loads in flight.
+#include "gf_device.h"
+
+namespace {
+
+enum : int {
+    F_G = 1,          // read gradients
+    F_RES = 2,        // read the historical gradient
+    F_SEND = 4,       // write wire(acc * S)
+    F_KEEP = 8,       // hg <- mu * acc
+    F_ZERO = 16,      // hg <- +0
+    F_L1 = 32         // accumulate |acc|
+};
+
+enum : int { MODE_ACCUM = 0, MODE_FUSED = 1, MODE_DENSE = 2, MODE_PACK = 3, MODE_SCALE = 4 };
+
+struct FuseArgs {
+    const void *const *tab;      // gradient pointer table (grads or pools)
+    int32_t tab_stride;          // m for grads, 1 for pools
+    int32_t use_pieces;          // 1: gather through the piece table
+    float *const *residual;
+    void *const *sendbuf;
+    const int32_t *slotmap;      // [n_tiles] rank among the selected chunks or -1; NULL: rank = tile
+    const int32_t *sel_idx;      // MODE_PACK: tiles to visit; NULL: all
+    float *chunk_l1;
+    const int32_t *piece_start;
+    const gf_piece *pieces;
+    int64_t N;
+    int32_t tile, n_tiles, units; // units: work items per worker
+    float S, mu;
+};
+
+template <int F, typename W>
+__device__ __forceinline__ void elem4(const gf_f32x4 g, const gf_f32x4 r, gf_f32x4 &res_out,
+                                      typename gf_wire4<W>::type &snd_out, float S, float mu, double &l1)
+{
+    float a0, a1, a2, a3;
+    if constexpr ((F & F_G) && (F & F_RES)) { a0 = g.x + r.x; a1 = g.y + r.y; a2 = g.z + r.z; a3 = g.w + r.w; }
+    else if constexpr (F & F_G) { a0 = g.x; a1 = g.y; a2 = g.z; a3 = g.w; }
+    else { a0 = r.x; a1 = r.y; a2 = r.z; a3 = r.w; }
+    if constexpr (F & F_L1) {
+        l1 += static_cast<double>(fabsf(a0));
+        l1 += static_cast<double>(fabsf(a1));
+        l1 += static_cast<double>(fabsf(a2));
+        l1 += static_cast<double>(fabsf(a3));
+    }
+    if constexpr (F & F_SEND)
+        snd_out = gf_pack4(gf_to_wire<W>(a0 * S), gf_to_wire<W>(a1 * S), gf_to_wire<W>(a2 * S), gf_to_wire<W>(a3 * S));
+    if constexpr (F & F_KEEP) res_out = gf_pack4(mu * a0, mu * a1, mu * a2, mu * a3);
+    if constexpr (F & F_ZERO) res_out = gf_pack4(0.f, 0.f, 0.f, 0.f);
+}
+
+// One contiguous run of `len` elements.  g / res / snd are already offset to
+// the run's first element; unused ones are null.
+template <int F, typename W>
+__device__ __forceinline__ void run(const float *g_, float *res_, W *snd_, int len, float S, float mu,
+                                    double &l1)
+{
+    const GF_GLOBAL float *__restrict__ g = gf_global(g_);
+    GF_GLOBAL float *__restrict__ res = gf_global(res_);
+    GF_GLOBAL W *__restrict__ snd = gf_global(snd_);
+    using W4 = typename gf_wire4<W>::type;
+    constexpr bool WRITES_RES = (F & (F_KEEP | F_ZERO)) != 0;
+    bool vec = true;
+    if constexpr (F & F_G) vec = vec && gf_aligned(g, 16);
+    if constexpr ((F & F_RES) || WRITES_RES) vec = vec && gf_aligned(res, 16);
+    if constexpr (F & F_SEND) vec = vec && gf_aligned(snd, sizeof(W4));
+    const int nvec = vec ? (len >> 2) : 0;
+    const GF_GLOBAL gf_f32x4 *g4 = reinterpret_cast<const GF_GLOBAL gf_f32x4 *>(g);
+    GF_GLOBAL gf_f32x4 *r4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(res);
+    GF_GLOBAL W4 *s4 = reinterpret_cast<GF_GLOBAL W4 *>(snd);
+
+    constexpr int U = 4;
+    int v = threadIdx.x;
+    for (; v + (U - 1) * GF_BLOCK < nvec; v += U * GF_BLOCK) {
+        gf_f32x4 gg[U], rr[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if constexpr (F & F_G) gg[u] = g4[v + u * GF_BLOCK];
+            if constexpr (F & F_RES) rr[u] = r4[v + u * GF_BLOCK];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            gf_f32x4 ro; W4 so;
+            elem4<F, W>(gg[u], rr[u], ro, so, S, mu, l1);
+            if constexpr (WRITES_RES) r4[v + u * GF_BLOCK] = ro;
+            if constexpr (F & F_SEND) s4[v + u * GF_BLOCK] = so;
+        }
+    }
+    for (; v < nvec; v += GF_BLOCK) {
+        gf_f32x4 gg = {}, rr = {}, ro; W4 so;
+        if constexpr (F & F_G) gg = g4[v];
+        if constexpr (F & F_RES) rr = r4[v];
+        elem4<F, W>(gg, rr, ro, so, S, mu, l1);
+        if constexpr (WRITES_RES) r4[v] = ro;
+        if constexpr (F & F_SEND) s4[v] = so;
+    }
+    for (int i = (nvec << 2) + threadIdx.x; i < len; i += GF_BLOCK) {   // unaligned run or ragged tail
+        float a;
+        if constexpr ((F & F_G) && (F & F_RES)) a = g[i] + res[i];
+        else if constexpr (F & F_G) a = g[i];
+        else a = res[i];
+        if constexpr (F & F_L1) l1 += static_cast<double>(fabsf(a));
+        if constexpr (F & F_SEND) snd[i] = gf_to_wire<W>(a * S);
+        if constexpr (F & F_KEEP) res[i] = mu * a;
+        if constexpr (F & F_ZERO) res[i] = 0.f;
+    }
+}
+
+template <int F, typename W>
+__device__ __forceinline__ void tile_body(const FuseArgs &a, int p, int tile, int64_t slot, double &l1)
+{
+    const int64_t tile_lo = static_cast<int64_t>(tile) * a.tile;
+    const int64_t left = a.N - tile_lo;
+    const int tile_len = left < a.tile ? static_cast<int>(left) : a.tile;
+    constexpr bool USES_RES = (F & (F_RES | F_KEEP | F_ZERO)) != 0;
+    float *res = USES_RES ? a.residual[p] + tile_lo : nullptr;
+    W *snd = (F & F_SEND) ? static_cast<W *>(a.sendbuf[p]) + slot * a.tile : nullptr;
+    if ((F & F_G) && a.use_pieces) {
+        const int pe = a.piece_start[tile + 1];
+        for (int i = a.piece_start[tile]; i < pe; ++i) {
+            const gf_piece pc = a.pieces[i];
+            const float *g = static_cast<const float *>(a.tab[static_cast<int64_t>(p) * a.tab_stride + pc.tensor]) + pc.src_off;
+            run<F, W>(g, USES_RES ? res + pc.dst_rel : nullptr, (F & F_SEND) ? snd + pc.dst_rel : nullptr,
+                      pc.len, a.S, a.mu, l1);
+        }
+    } else {
+        const float *g = (F & F_G) ? static_cast<const float *>(a.tab[p]) + tile_lo : nullptr;
+        run<F, W>(g, res, snd, tile_len, a.S, a.mu, l1);
+    }
+}
+
+template <int MODE, typename W>
+__global__ __launch_bounds__(GF_BLOCK) void k_fuse(const FuseArgs a)
+{
+    const int p = blockIdx.x / a.units;
+    const int u = blockIdx.x - p * a.units;
+    int tile = u;
+    int64_t slot = u;
+    if constexpr (MODE == MODE_PACK) {
+        if (a.sel_idx) tile = a.sel_idx[u];
+    } else if constexpr (MODE == MODE_FUSED || MODE == MODE_SCALE) {
+        if (a.slotmap) slot = a.slotmap[tile];
+    }
+    double l1 = 0.0;
+    if constexpr (MODE == MODE_ACCUM) tile_body<F_G | F_RES | F_KEEP | F_L1, W>(a, p, tile, 0, l1);   // mu = 1 here
+    if constexpr (MODE == MODE_FUSED) {
+        if (slot >= 0) tile_body<F_G | F_RES | F_SEND | F_ZERO | F_L1, W>(a, p, tile, slot, l1);
+        else tile_body<F_G | F_RES | F_KEEP | F_L1, W>(a, p, tile, 0, l1);
+    }
+    if constexpr (MODE == MODE_DENSE) tile_body<F_G | F_SEND, W>(a, p, tile, slot, l1);
+    if constexpr (MODE == MODE_PACK) tile_body<F_RES | F_SEND | F_ZERO, W>(a, p, tile, slot, l1);
+    if constexpr (MODE == MODE_SCALE) {
+        if (slot < 0) tile_body<F_RES | F_KEEP, W>(a, p, tile, 0, l1);
+    }
+    if constexpr (MODE == MODE_ACCUM || MODE == MODE_FUSED) {
+        const double s = gf_block_sum<GF_BLOCK>(l1);
+        if (a.chunk_l1 && threadIdx.x == 0)
+            a.chunk_l1[static_cast<int64_t>(p) * a.n_tiles + tile] = static_cast<float>(s);
+    }
+}
+
+// slotmap[c] = rank of chunk c in the ascending selection, or -1.
+__global__ __launch_bounds__(GF_BLOCK) void k_slotmap(const int32_t *__restrict__ sel, int32_t k,
+                                                      int32_t n_chunks, int32_t *__restrict__ slotmap)
+{
+    const int c = blockIdx.x * GF_BLOCK + threadIdx.x;
+    if (c >= n_chunks) return;
+    int lo = 0, hi = k;                       // first position with sel[pos] >= c
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (sel[mid] < c) lo = mid + 1; else hi = mid;
+    }
+    slotmap[c] = (lo < k && sel[lo] == c) ? lo : -1;
+}
+
+template <int MODE>
+gf_status launch(const gf_plan *pl, const FuseArgs &a, int64_t blocks, hipStream_t st)
+{
+    if (blocks <= 0) return GF_OK;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(GF_BLOCK);
+    if (pl->wire == GF_WIRE_F16) hipLaunchKernelGGL((k_fuse<MODE, uint16_t>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((k_fuse<MODE, float>), grid, block, 0, st, a);
+    GF_LAUNCH_CHECK();
+    return GF_OK;
+}
+
+}  // namespace
+
+extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
+                                  const void *const *grads, const float *const *pools,
+                                  float *const *residual,
+                                  const int32_t *sel_idx, int32_t k,
+                                  float loss_scale, float mu,
+                                  void *const *sendbuf, float *chunk_l1,
+                                  void *workspace, gf_stream stream)
+{
+    if (!pl) return GF_EINVAL;
+    if (phase == 0 || (phase & ~(GF_PHASE_ACCUM | GF_PHASE_PACK))) return GF_EINVAL;
+    const bool accum = phase & GF_PHASE_ACCUM, pack = phase & GF_PHASE_PACK;
+    if (accum && ((grads != nullptr) == (pools != nullptr))) return GF_EINVAL;
+    if (pack && !sendbuf) return GF_EINVAL;
+    if (!residual && (!(accum && pack) || sel_idx || chunk_l1)) return GF_EINVAL;
+    if ((sel_idx || chunk_l1) && pl->chunk == 0) return GF_EINVAL;
+    if (chunk_l1 && !accum) return GF_EINVAL;
+    if (sel_idx && pack && (k < 1 || k > pl->n_chunks)) return GF_EINVAL;
+    const bool need_map = sel_idx && pack && (accum || mu != 1.0f);
+    if (need_map && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return GF_EINVAL;
+    if (!pl->on_device) return GF_ESTATE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    FuseArgs a{};
+    a.tab = grads ? grads : reinterpret_cast<const void *const *>(pools);
+    a.tab_stride = grads ? pl->m : 1;
+    a.use_pieces = grads ? 1 : 0;
+    a.residual = residual;
+    a.sendbuf = sendbuf;
+    a.chunk_l1 = chunk_l1;
+    a.piece_start = pl->d_piece_start;
+    a.pieces = pl->d_pieces;
+    a.N = pl->N;
+    a.tile = pl->tile;
+    a.n_tiles = pl->n_tiles;
+    a.units = pl->n_tiles;
+    a.S = loss_scale;
+    a.mu = mu;
+
+    int32_t *slotmap = nullptr;
+    if (need_map) {
+        slotmap = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + gf_ws_slotmap_off());
+        hipLaunchKernelGGL(k_slotmap, dim3((pl->n_chunks + GF_BLOCK - 1) / GF_BLOCK), dim3(GF_BLOCK), 0, st,
+                           sel_idx, k, pl->n_chunks, slotmap);
+        GF_LAUNCH_CHECK();
+    }
+    const int64_t all = static_cast<int64_t>(pl->P) * pl->n_tiles;
+
+    if (accum && !pack) {
+        a.mu = 1.0f;                         // hg <- acc
+        return launch<MODE_ACCUM>(pl, a, all, st);
+    }
+    if (accum && pack) {
+        if (!residual) return launch<MODE_DENSE>(pl, a, all, st);
+        a.slotmap = slotmap;                 // null: every chunk is sent, rank = chunk index
+        return launch<MODE_FUSED>(pl, a, all, st);
+    }
+    // pack only: visit the selected chunks; the rest only if mu scales them
+    a.sel_idx = sel_idx;
+    a.units = sel_idx ? k : pl->n_tiles;
+    gf_status rc = launch<MODE_PACK>(pl, a, static_cast<int64_t>(pl->P) * a.units, st);
+    if (rc != GF_OK || !sel_idx || mu == 1.0f) return rc;
+    a.units = pl->n_tiles;
+    a.slotmap = slotmap;
+    return launch<MODE_SCALE>(pl, a, all, st);
+}

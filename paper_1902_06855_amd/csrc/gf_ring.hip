@@ -1,0 +1,164 @@
+// gf_ring_reduce_sim: the elementwise arithmetic of ring allreduce
+// (Section 2.4) over P send buffers resident in this GPU's memory.
+//
+// Reduce-scatter hop t moves segment (r - t) mod P from rank r to rank r + 1,
+// which adds its own values and rounds to the wire type; segment s therefore
+// ends as the left fold x_s + x_{s+1} + ... + x_{s-1}.  The kernel computes
+// that fold directly: one thread owns 16 bytes of one segment, reads the same
+// 16 bytes from all P buffers starting at worker s, and writes the result once
+// (plus P copies when the all-gather outputs are requested).  A workgroup never
+// crosses a segment border, so s and the P base pointers are wave-uniform.
+#include "gf_device.h"
+
+namespace {
+
+struct RingArgs {
+    const void *const *send;
+    void *reduced;
+    void *const *allgather;
+    const gf_bucket_dev *buckets;     // dense plans
+    const gf_ring_block *blocks;      // dense plans
+    const int64_t *L_dev;
+    int64_t L;
+    int32_t P;
+    int32_t blocks_per_segment;       // single-ring launches
+};
+
+template <typename W> struct vec16;
+template <> struct vec16<uint16_t> { using type = gf_u32x4; static constexpr int n = 8; };
+template <> struct vec16<float> { using type = gf_f32x4; static constexpr int n = 4; };
+
+__device__ __forceinline__ gf_u32x4 hop16(gf_u32x4 a, gf_u32x4 b)
+{
+    gf_u32x4 r = {gf_hop_add_h2(a.x, b.x), gf_hop_add_h2(a.y, b.y),
+                  gf_hop_add_h2(a.z, b.z), gf_hop_add_h2(a.w, b.w)};
+    return r;
+}
+__device__ __forceinline__ gf_f32x4 hop16(gf_f32x4 a, gf_f32x4 b)
+{
+    gf_f32x4 r = {a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w};
+    return r;
+}
+
+template <typename W, bool DENSE>
+__global__ __launch_bounds__(GF_BLOCK) void k_ring(const RingArgs a)
+{
+    using V = typename vec16<W>::type;
+    constexpr int A = vec16<W>::n;
+    const int P = a.P;
+    int64_t lo, hi, seg;
+    int s, bis;
+    if constexpr (DENSE) {
+        const gf_ring_block rb = a.blocks[blockIdx.x];
+        const gf_bucket_dev bk = a.buckets[rb.bucket];
+        lo = bk.lo; hi = bk.hi; seg = bk.seg;
+        s = rb.segment; bis = rb.block_in_segment;
+    } else {
+        int64_t L = a.L;
+        if (a.L_dev) { const int64_t d = *a.L_dev; L = d < 0 ? 0 : (d < L ? d : L); }
+        lo = 0; hi = L;
+        const int64_t per = (L + P - 1) / P;
+        seg = (per + A - 1) / A * A;
+        s = blockIdx.x / a.blocks_per_segment;
+        bis = blockIdx.x - s * a.blocks_per_segment;
+    }
+    const int64_t Lb = hi - lo;
+    int64_t seg_lo = static_cast<int64_t>(s) * seg; if (seg_lo > Lb) seg_lo = Lb;
+    int64_t seg_hi = seg_lo + seg; if (seg_hi > Lb) seg_hi = Lb;
+    seg_lo += lo; seg_hi += lo;
+    const int64_t e = seg_lo + (static_cast<int64_t>(bis) * GF_RING_GROUPS_PER_BLOCK + threadIdx.x) * A;
+    if (e >= seg_hi) return;
+    const int n = seg_hi - e < A ? static_cast<int>(seg_hi - e) : A;
+
+    // 128-bit path needs every buffer 16-byte aligned at this offset.  All
+    // offsets of a segment differ from seg_lo by multiples of 16 bytes.
+    unsigned mis = static_cast<unsigned>((seg_lo * sizeof(W)) & 15);
+    for (int q = 0; q < P; ++q) mis |= static_cast<unsigned>(reinterpret_cast<uintptr_t>(a.send[q]) & 15);
+    mis |= static_cast<unsigned>(reinterpret_cast<uintptr_t>(a.reduced) & 15);
+    if (a.allgather)
+        for (int q = 0; q < P; ++q) mis |= static_cast<unsigned>(reinterpret_cast<uintptr_t>(a.allgather[q]) & 15);
+
+    if (mis == 0 && n == A) {
+        int q = s;
+        V v = *reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e);
+        int j = 1;
+        constexpr int U = 8;
+        for (; j + U - 1 < P; j += U) {
+            V x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                q = q + 1 == P ? 0 : q + 1;
+                x[u] = *reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) v = hop16(v, x[u]);
+        }
+        for (; j < P; ++j) {
+            q = q + 1 == P ? 0 : q + 1;
+            v = hop16(v, *reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e));
+        }
+        *reinterpret_cast<GF_GLOBAL V *>(gf_global(static_cast<W *>(a.reduced)) + e) = v;
+        if (a.allgather)
+            for (int r = 0; r < P; ++r) *reinterpret_cast<GF_GLOBAL V *>(gf_global(static_cast<W *>(a.allgather[r])) + e) = v;
+    } else {
+        for (int i = 0; i < n; ++i) {
+            int q = s;
+            W v = static_cast<const W *>(a.send[q])[e + i];
+            for (int j = 1; j < P; ++j) {
+                q = q + 1 == P ? 0 : q + 1;
+                v = gf_hop_add(v, static_cast<const W *>(a.send[q])[e + i]);
+            }
+            static_cast<W *>(a.reduced)[e + i] = v;
+            if (a.allgather)
+                for (int r = 0; r < P; ++r) static_cast<W *>(a.allgather[r])[e + i] = v;
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *sendbuf, int64_t L,
+                                        const int64_t *L_dev, void *reduced, void *const *allgather_out,
+                                        void *workspace, gf_stream stream)
+{
+    (void)workspace;
+    if (!pl || !sendbuf || !reduced || L < 0) return GF_EINVAL;
+    const bool dense = pl->chunk == 0;
+    if (dense && (L != pl->N || L_dev)) return GF_EINVAL;
+    if (!dense && L > static_cast<int64_t>(pl->n_chunks) * pl->chunk) return GF_EINVAL;
+    if (!pl->on_device) return GF_ESTATE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    RingArgs a{};
+    a.send = sendbuf;
+    a.reduced = reduced;
+    a.allgather = allgather_out;
+    a.L = L;
+    a.L_dev = L_dev;
+    a.P = pl->P;
+    if (dense) {
+        a.buckets = pl->d_buckets;
+        a.blocks = pl->d_ring_blocks;
+        const size_t nb = pl->ring_blocks.size();
+        if (nb == 0) return GF_OK;
+        if (pl->wire == GF_WIRE_F16)
+            hipLaunchKernelGGL((k_ring<uint16_t, true>), dim3(static_cast<unsigned>(nb)), dim3(GF_BLOCK), 0, st, a);
+        else
+            hipLaunchKernelGGL((k_ring<float, true>), dim3(static_cast<unsigned>(nb)), dim3(GF_BLOCK), 0, st, a);
+    } else {
+        if (L == 0) return GF_OK;
+        const int64_t A = gf_wire_granule(pl->wire);
+        const int64_t seg = gf_ring_segment_len(L, pl->P, pl->wire);   // upper bound when L_dev is used
+        const int64_t groups = seg / A;
+        const int64_t bps = (groups + GF_RING_GROUPS_PER_BLOCK - 1) / GF_RING_GROUPS_PER_BLOCK;
+        if (bps * pl->P > (int64_t{1} << 30)) return GF_EINVAL;
+        a.blocks_per_segment = static_cast<int32_t>(bps);
+        const dim3 grid(static_cast<unsigned>(bps * pl->P));
+        if (pl->wire == GF_WIRE_F16)
+            hipLaunchKernelGGL((k_ring<uint16_t, false>), grid, dim3(GF_BLOCK), 0, st, a);
+        else
+            hipLaunchKernelGGL((k_ring<float, false>), grid, dim3(GF_BLOCK), 0, st, a);
+    }
+    GF_LAUNCH_CHECK();
+    return GF_OK;
+}

@@ -1,0 +1,171 @@
+// gf_chunk_score_select: importance scores and the important-chunk set of
+// Section 3.2.  The paper exchanges the per-chunk norms with a small allreduce;
+// with all P norm rows in one memory that is a column sum.  The k largest
+// scores are then found by a most-significant-byte-first radix select in LDS
+// (no sort, no host round trip) and emitted in ascending chunk order by an
+// ordered compaction; equal scores go to the lower chunk index.
+#include "gf_device.h"
+
+namespace {
+
+constexpr int SEL_T = 1024;   // threads of the single selecting workgroup
+
+__global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1, int32_t P, int32_t nc,
+                                                    float *__restrict__ score)
+{
+    const int c = blockIdx.x * GF_BLOCK + threadIdx.x;
+    if (c >= nc) return;
+    double s = 0.0;
+    for (int p = 0; p < P; ++p) s += static_cast<double>(l1[static_cast<int64_t>(p) * nc + c]);
+    score[c] = static_cast<float>(s);
+}
+
+// Chunks that went through this iteration's allreduce: each GPU divides the
+// norm of the (identical) reduced values by the GPU count, then the norms are
+// summed over GPUs.
+__global__ __launch_bounds__(GF_BLOCK) void k_score_sent(const float *__restrict__ red_l1,
+                                                         const int32_t *__restrict__ prev_sel, int32_t k_prev,
+                                                         int32_t P, float *__restrict__ score)
+{
+    const int j = blockIdx.x * GF_BLOCK + threadIdx.x;
+    if (j >= k_prev) return;
+    const double share = static_cast<double>(red_l1[j]) / static_cast<double>(P);
+    double s = 0.0;
+    for (int p = 0; p < P; ++p) s += share;
+    score[prev_sel[j]] = static_cast<float>(s);
+}
+
+// Monotone map from float order to unsigned order.
+__device__ __forceinline__ uint32_t ord_key(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan over the SEL_T threads; *total receives the sum (all threads).
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t incl = wave_incl_scan(v);
+    __syncthreads();                               // wave_tot may still be read from a previous call
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < SEL_T / 64; ++w) {
+        const uint32_t t = wave_tot[w];
+        if (w < wave) before += t;
+        all += t;
+    }
+    *total = all;
+    return before + incl - v;
+}
+
+__global__ __launch_bounds__(SEL_T) void k_select(const float *__restrict__ score, int32_t nc, int32_t k,
+                                                  int32_t C, int64_t N,
+                                                  int32_t *__restrict__ sel, uint8_t *__restrict__ mask,
+                                                  int64_t *__restrict__ packed_len)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wave_tot[SEL_T / 64];
+    __shared__ uint32_t s_bin, s_remaining;
+    const int tid = threadIdx.x;
+
+    // ---- key of the k-th largest score, one byte per pass
+    uint32_t prefix = 0, decided = 0, remaining = static_cast<uint32_t>(k);
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int c = tid; c < nc; c += SEL_T) {
+            const uint32_t key = ord_key(score[c]);
+            if ((key & decided) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        // thread t looks at bin 255 - t: a prefix sum over t is a count of keys in higher bins
+        const uint32_t mine = tid < 256 ? hist[255 - tid] : 0u;
+        uint32_t total;
+        const uint32_t above = block_excl_scan(mine, wave_tot, &total);
+        if (tid < 256 && above < remaining && above + mine >= remaining) {
+            s_bin = static_cast<uint32_t>(255 - tid);
+            s_remaining = remaining - above;
+        }
+        __syncthreads();
+        prefix |= s_bin << shift;
+        decided |= 255u << shift;
+        remaining = s_remaining;
+        __syncthreads();
+    }
+    const uint32_t T = prefix;            // every key above T is taken
+    const uint32_t r = remaining;         // plus the first r chunks whose key equals T
+
+    // ---- ordered compaction
+    uint32_t gt_base = 0, eq_base = 0;
+    for (int base = 0; base < nc; base += SEL_T) {
+        const int c = base + tid;
+        uint32_t gt = 0, eq = 0;
+        if (c < nc) {
+            const uint32_t key = ord_key(score[c]);
+            gt = key > T;
+            eq = key == T;
+        }
+        uint32_t total;
+        const uint32_t ex = block_excl_scan(gt | (eq << 16), wave_tot, &total);
+        const uint32_t gt_before = gt_base + (ex & 0xffffu);
+        const uint32_t eq_before = eq_base + (ex >> 16);
+        if (c < nc) {
+            const bool take = gt || (eq && eq_before < r);
+            if (take) sel[gt_before + (eq_before < r ? eq_before : r)] = c;
+            if (mask) mask[c] = take ? 1 : 0;
+            if (packed_len && c == nc - 1) {
+                const int64_t last_len = N - static_cast<int64_t>(nc - 1) * C;
+                *packed_len = static_cast<int64_t>(k) * C - (take ? C - last_len : 0);
+            }
+        }
+        gt_base += total & 0xffffu;
+        eq_base += total >> 16;
+    }
+}
+
+}  // namespace
+
+extern "C" gf_status gf_chunk_score_select(const gf_plan *pl, const float *chunk_l1,
+                                           const float *reduced_l1, const int32_t *prev_sel, int32_t k_prev,
+                                           int32_t k, float *scores, int32_t *sel_idx, uint8_t *mask,
+                                           int64_t *packed_len, void *workspace, gf_stream stream)
+{
+    if (!pl || !chunk_l1 || !sel_idx) return GF_EINVAL;
+    if (pl->chunk == 0 || k < 1 || k > pl->n_chunks) return GF_EINVAL;
+    if (prev_sel && (!reduced_l1 || k_prev < 1 || k_prev > pl->n_chunks)) return GF_EINVAL;
+    // the score vector lives in the workspace when the caller does not want it
+    if (!scores) {
+        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return GF_EINVAL;
+        scores = reinterpret_cast<float *>(static_cast<char *>(workspace) + gf_ws_scores_off(pl));
+    }
+    if (!pl->on_device) return GF_ESTATE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t nc = pl->n_chunks;
+
+    hipLaunchKernelGGL(k_score, dim3((nc + GF_BLOCK - 1) / GF_BLOCK), dim3(GF_BLOCK), 0, st,
+                       chunk_l1, pl->P, nc, scores);
+    GF_LAUNCH_CHECK();
+    if (prev_sel) {
+        hipLaunchKernelGGL(k_score_sent, dim3((k_prev + GF_BLOCK - 1) / GF_BLOCK), dim3(GF_BLOCK), 0, st,
+                           reduced_l1, prev_sel, k_prev, pl->P, scores);
+        GF_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_T), 0, st,
+                       scores, nc, k, pl->chunk, pl->N, sel_idx, mask, packed_len);
+    GF_LAUNCH_CHECK();
+    return GF_OK;
+}

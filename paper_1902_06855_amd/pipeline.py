@@ -1,0 +1,146 @@
+"""One simulated iteration of the path, as calls into the C-ABI library.
+
+`Pipeline` owns the device buffers of a run (through PyTorch, used only as an
+allocator) and strings the four entry points together in the order of
+Sections 3.1-3.2 of the paper.  It computes nothing itself.
+
+Schedules for a plan with chunks (coarse-grained sparse communication):
+  "lagged"     the paper's: the chunks sent at iteration t were chosen at the
+               end of iteration t-1, so accumulate, norms, pack and the
+               historical-gradient rule are one pass (gf_fuse_pack with both
+               phases).  Iteration 0 chooses from its own accumulated gradients.
+  "immediate"  every iteration chooses from its own accumulated gradients:
+               accumulate pass, select, pack pass.
+A dense plan (chunk = 0) runs cast -> per-bucket ring -> cast back.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import gf
+
+
+class Pipeline:
+    def __init__(self, sizes: Sequence[int], P: int, chunk: int, theta: int, loss_scale: float,
+                 k: int = 0, mu: float = 1.0, wire: str = "f16", schedule: str = "lagged",
+                 scatter_out: bool = False, allgather: bool = False, device: str = "cuda"):
+        assert schedule in ("lagged", "immediate")
+        self.sizes, self.P, self.chunk, self.mu = list(sizes), int(P), int(chunk), float(mu)
+        self.S, self.schedule, self.device = float(loss_scale), schedule, device
+        self.alpha = float(np.float32(1.0) / np.float32(loss_scale))   # 1/S rounded once to fp32
+        self.wire = gf.GF_WIRE_F16 if wire == "f16" else gf.GF_WIRE_F32
+        self.wdtype = torch.float16 if wire == "f16" else torch.float32
+        self.plan = gf.Plan(self.sizes, min(int(theta), 1 << 60), self.chunk, self.P, self.wire)
+        self.N, self.n_chunks, self.m = self.plan.N, self.plan.n_chunks, len(self.sizes)
+        self.k = int(k) if self.chunk else 0
+        self.ws = self.plan.workspace()
+        self.t = 0
+        new = lambda n, dt: torch.zeros(n, dtype=dt, device=device)
+        if self.chunk:
+            assert 1 <= self.k <= self.n_chunks
+            self.cap = self.k * self.chunk                      # packed-buffer capacity, elements
+            self.residual = [new(self.N, torch.float32) for _ in range(self.P)]
+            self.residual_tab = gf.ptr_table(self.residual, device)
+            self.l1 = new(self.P * self.n_chunks, torch.float32)
+            self.scores = new(self.n_chunks, torch.float32)
+            self.sel = new(self.k, torch.int32)
+            self.mask = new(self.n_chunks, torch.uint8)
+            self.packed_len = new(1, torch.int64)
+            self.red_l1 = new(self.k, torch.float32)
+        else:
+            self.cap = self.N
+            self.residual = None
+        self.send = [new(self.cap, self.wdtype) for _ in range(self.P)]
+        self.send_tab = gf.ptr_table(self.send, device)
+        self.reduced = new(self.cap, self.wdtype)
+        self.out_pool = new(self.N, torch.float32)
+        self.out_tensors = self.out_tab = None
+        if scatter_out:
+            self.out_tensors = [new(s, torch.float32) for s in self.sizes]
+            self.out_tab = gf.ptr_table(self.out_tensors, device)
+        self.ag = self.ag_tab = None
+        if allgather:
+            self.ag = [new(self.cap, self.wdtype) for _ in range(self.P)]
+            self.ag_tab = gf.ptr_table(self.ag, device)
+        self.grads_tab = self.pools_tab = None
+        self._keep = None
+
+    # ------------------------------------------------------------- inputs
+    def set_gradients(self, grads: List[List[torch.Tensor]]) -> None:
+        """grads[p][l]: scattered fp32 device tensors in ID order (fusion happens in the read)."""
+        flat = [t for row in grads for t in row]
+        assert len(flat) == self.P * self.m
+        self._keep = grads
+        self.grads_tab, self.pools_tab = gf.ptr_table(flat, self.device), None
+
+    def set_pools(self, pools: List[torch.Tensor]) -> None:
+        """pools[p]: N-element fp32 pools already in generation order (zero-copy lazy allreduce)."""
+        assert len(pools) == self.P and all(p.numel() == self.N for p in pools)
+        self._keep = pools
+        self.pools_tab, self.grads_tab = gf.ptr_table(pools, self.device), None
+
+    def use_tables(self, grads_tab: Optional[torch.Tensor], pools_tab: Optional[torch.Tensor]) -> None:
+        """Switch to pointer tables prepared earlier (no allocation, no copy)."""
+        self.grads_tab, self.pools_tab = grads_tab, pools_tab
+
+    # ------------------------------------------------------------- stages
+    def accum(self) -> None:
+        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_ACCUM, grads=self.grads_tab, pools=self.pools_tab,
+                        residual=self.residual_tab, chunk_l1=self.l1, workspace=self.ws)
+
+    def select(self, after_allreduce: bool) -> None:
+        """Choose self.sel (in place); after_allreduce scores the chunks just sent by their reduced norm."""
+        if after_allreduce:
+            gf.gf_chunk_score_select(self.plan, self.l1, reduced_l1=self.red_l1, prev_sel=self.sel, k_prev=self.k,
+                                     k=self.k, scores=self.scores, sel_idx=self.sel, mask=self.mask,
+                                     packed_len=self.packed_len, workspace=self.ws)
+        else:
+            gf.gf_chunk_score_select(self.plan, self.l1, k=self.k, scores=self.scores, sel_idx=self.sel,
+                                     mask=self.mask, packed_len=self.packed_len, workspace=self.ws)
+
+    def pack(self) -> None:
+        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_PACK, residual=self.residual_tab, sel_idx=self.sel, k=self.k,
+                        loss_scale=self.S, mu=self.mu, sendbuf=self.send_tab, workspace=self.ws)
+
+    def fused(self) -> None:
+        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_ACCUM | gf.GF_PHASE_PACK, grads=self.grads_tab,
+                        pools=self.pools_tab, residual=self.residual_tab, sel_idx=self.sel, k=self.k,
+                        loss_scale=self.S, mu=self.mu, sendbuf=self.send_tab, chunk_l1=self.l1,
+                        workspace=self.ws)
+
+    def cast_dense(self) -> None:
+        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_ACCUM | gf.GF_PHASE_PACK, grads=self.grads_tab,
+                        pools=self.pools_tab, loss_scale=self.S, sendbuf=self.send_tab, workspace=self.ws)
+
+    def ring(self) -> None:
+        if self.chunk:   # the packed length stays on the device
+            gf.gf_ring_reduce_sim(self.plan, self.send_tab, self.cap, self.reduced, L_dev=self.packed_len,
+                                  allgather_out=self.ag_tab, workspace=self.ws)
+        else:
+            gf.gf_ring_reduce_sim(self.plan, self.send_tab, self.N, self.reduced, allgather_out=self.ag_tab,
+                                  workspace=self.ws)
+
+    def unpack(self) -> None:
+        if self.chunk:
+            gf.gf_unpack_apply(self.plan, self.reduced, self.cap, sel_idx=self.sel, k=self.k, alpha=self.alpha,
+                               out_pool=self.out_pool, out_tensors=self.out_tab, reduced_l1=self.red_l1,
+                               workspace=self.ws)
+        else:
+            gf.gf_unpack_apply(self.plan, self.reduced, self.N, alpha=self.alpha, out_pool=self.out_pool,
+                               out_tensors=self.out_tab, workspace=self.ws)
+
+    # ---------------------------------------------------------- iteration
+    def step(self) -> None:
+        """One whole iteration on the current stream; returns without synchronising."""
+        if not self.chunk:
+            self.cast_dense(); self.ring(); self.unpack()
+        elif self.schedule == "immediate" or self.t == 0:
+            self.accum(); self.select(False); self.pack(); self.ring(); self.unpack()
+            if self.schedule == "lagged":
+                self.select(True)
+        else:
+            self.fused(); self.ring(); self.unpack(); self.select(True)
+        self.t += 1

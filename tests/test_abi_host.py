@@ -1,0 +1,157 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what include/gf.h
+declares, plans exactly like the CPU checker, and rejects bad calls with
+status codes.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import binding as ob
+from paper_1902_06855_amd import workloads as wl
+
+gf = pytest.importorskip("paper_1902_06855_amd.gf")
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "gf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gf_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert len(names) >= 14 and {"gf_fuse_pack", "gf_chunk_score_select", "gf_ring_reduce_sim",
+                                 "gf_unpack_apply"} <= set(names)
+    lib = ctypes.CDLL(gf.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in gf.h but not exported"
+    assert set(names) == set(gf.EXPORTS)
+
+
+def test_status_strings():
+    for code in range(5):
+        assert gf.gf_status_string(code).startswith("GF_")
+    assert "unknown" in gf.gf_status_string(99)
+
+
+@pytest.mark.parametrize("name", ["tiny", "alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb",
+                                  "alexnet_csc", "resnet50_csc"])
+def test_plan_matches_the_checker(name):
+    w = wl.config(name)
+    plan = gf.Plan(w.sizes, min(w.theta, 1 << 60), w.chunk, w.P, to_device=False)
+    off, lo, hi = plan.layout()
+    o_off, o_N = ob.layout(w.sizes)
+    o_lo, o_hi = ob.buckets(w.sizes, w.theta)
+    assert plan.N == o_N and off == list(o_off)
+    assert lo == list(o_lo) and hi == list(o_hi) and plan.n_buckets == len(o_lo)
+    if w.chunk:
+        assert plan.n_chunks == ob.n_chunks(w.N, w.chunk) == plan.tiles()
+    else:
+        assert plan.n_chunks == 0
+    for L in (0, 1, 7, 8, 1000, w.N // 3, w.N):
+        assert plan.ring_segment(L) == ob.ring_segment(L, w.P, "f16")
+    plan.close()
+
+
+def test_ring_segment_fp32_wire():
+    plan = gf.Plan([100, 200], 1 << 40, 0, 6, wire=gf.GF_WIRE_F32, to_device=False)
+    for L in (0, 1, 5, 24, 25, 300):
+        assert plan.ring_segment(L) == ob.ring_segment(L, 6, "f32")
+    assert plan.ring_segment(-1) == -1
+
+
+@pytest.mark.parametrize("sizes,chunk", [([7, 1, 64, 333, 2, 1024, 5], 96), ([50, 8, 700, 33, 1200, 64, 5], 0),
+                                         (wl.resnet50_sizes(), 8192), ([5], 3), ([3, 3, 3], 3)])
+def test_tile_pieces_tile_the_pool_in_generation_order(sizes, chunk):
+    plan = gf.Plan(sizes, 1 << 40, chunk, 2, to_device=False)
+    off, N = ob.layout(sizes)
+    owner = np.empty(N, dtype=np.int64)        # which tensor / element each pool slot holds
+    elem = np.empty(N, dtype=np.int64)
+    for j, s in enumerate(sizes):
+        owner[off[j]:off[j] + s] = j
+        elem[off[j]:off[j] + s] = np.arange(s)
+    T = chunk if chunk else 8192
+    assert plan.tiles() == -(-N // T)
+    pos = 0
+    for t in range(plan.tiles()):
+        assert pos == t * T
+        for (tensor, src, ln) in plan.tile_pieces(t):
+            assert ln >= 1
+            assert np.all(owner[pos:pos + ln] == tensor)
+            assert np.array_equal(elem[pos:pos + ln], np.arange(src, src + ln))
+            pos += ln
+        assert pos == min(N, (t + 1) * T)
+    assert pos == N
+
+
+def test_plan_create_rejects_bad_arguments():
+    bad = [
+        dict(tensor_numel=[], theta_elems=1, chunk_elems=0, P=1),
+        dict(tensor_numel=[4, 0], theta_elems=1, chunk_elems=0, P=1),
+        dict(tensor_numel=[4], theta_elems=-1, chunk_elems=0, P=1),
+        dict(tensor_numel=[4], theta_elems=1, chunk_elems=-2, P=1),
+        dict(tensor_numel=[4], theta_elems=1, chunk_elems=0, P=0),
+        dict(tensor_numel=[4], theta_elems=1, chunk_elems=0, P=5000),
+        dict(tensor_numel=[4], theta_elems=1, chunk_elems=0, P=1, wire=7),
+    ]
+    for kw in bad:
+        with pytest.raises(gf.GfError) as e:
+            gf.Plan(to_device=False, **kw)
+        assert e.value.status == gf.GF_EINVAL
+
+
+def test_compute_calls_validate_before_touching_the_gpu():
+    csc = gf.Plan([4096, 4096], 1 << 40, 1024, 2, to_device=False)
+    dense = gf.Plan([4096, 4096], 1 << 40, 0, 2, to_device=False)
+    fake = 0x1000                     # never dereferenced: validation fails first
+    E, S = gf.GF_EINVAL, gf.GF_ESTATE
+
+    def status(fn, *a, **kw):
+        with pytest.raises(gf.GfError) as e:
+            fn(*a, stream=0, **kw)
+        return e.value.status
+
+    # fuse_pack
+    assert status(gf.gf_fuse_pack, csc, 0, pools=fake, residual=fake, sendbuf=fake) == E
+    assert status(gf.gf_fuse_pack, csc, 3, residual=fake, sendbuf=fake) == E               # no gradients
+    assert status(gf.gf_fuse_pack, csc, 3, grads=fake, pools=fake, residual=fake, sendbuf=fake) == E
+    assert status(gf.gf_fuse_pack, csc, 3, pools=fake, residual=fake) == E                 # no send buffer
+    assert status(gf.gf_fuse_pack, csc, 1, pools=fake) == E                                # dense needs both phases
+    assert status(gf.gf_fuse_pack, csc, 3, pools=fake, sel_idx=fake, k=1, sendbuf=fake) == E  # sparse needs hg
+    assert status(gf.gf_fuse_pack, dense, 3, pools=fake, residual=fake, sel_idx=fake, k=1, sendbuf=fake) == E
+    assert status(gf.gf_fuse_pack, dense, 3, pools=fake, residual=fake, chunk_l1=fake, sendbuf=fake) == E
+    assert status(gf.gf_fuse_pack, csc, 3, pools=fake, residual=fake, sel_idx=fake, k=0, sendbuf=fake,
+                  workspace=0x100) == E
+    assert status(gf.gf_fuse_pack, csc, 3, pools=fake, residual=fake, sel_idx=fake, k=9, sendbuf=fake,
+                  workspace=0x100) == E
+    assert status(gf.gf_fuse_pack, csc, 3, pools=fake, residual=fake, sel_idx=fake, k=2, sendbuf=fake) == E  # no workspace
+    assert status(gf.gf_fuse_pack, csc, 3, pools=fake, residual=fake, sel_idx=fake, k=2, sendbuf=fake,
+                  workspace=0x104) == E                                                    # misaligned workspace
+    assert status(gf.gf_fuse_pack, csc, 3, pools=fake, residual=fake, sel_idx=fake, k=2, sendbuf=fake,
+                  workspace=0x100) == S                                                    # valid, but not uploaded
+    assert status(gf.gf_fuse_pack, dense, 3, pools=fake, sendbuf=fake) == S
+    # select
+    assert status(gf.gf_chunk_score_select, csc, fake, k=0, sel_idx=fake, scores=fake) == E
+    assert status(gf.gf_chunk_score_select, csc, fake, k=9, sel_idx=fake, scores=fake) == E
+    assert status(gf.gf_chunk_score_select, dense, fake, k=1, sel_idx=fake, scores=fake) == E
+    assert status(gf.gf_chunk_score_select, csc, fake, k=1, sel_idx=fake, prev_sel=fake, k_prev=1, scores=fake) == E
+    assert status(gf.gf_chunk_score_select, csc, fake, k=1, sel_idx=fake) == E             # scores need workspace
+    assert status(gf.gf_chunk_score_select, csc, fake, k=1, sel_idx=fake, scores=fake) == S
+    # ring
+    assert status(gf.gf_ring_reduce_sim, csc, fake, -1, fake) == E
+    assert status(gf.gf_ring_reduce_sim, csc, fake, 8193, fake) == E
+    assert status(gf.gf_ring_reduce_sim, dense, fake, 100, fake) == E                      # dense reduces all N
+    assert status(gf.gf_ring_reduce_sim, dense, fake, 8192, fake, L_dev=fake) == E
+    assert status(gf.gf_ring_reduce_sim, dense, fake, 8192, fake) == S
+    assert status(gf.gf_ring_reduce_sim, csc, fake, 2048, fake, L_dev=fake) == S
+    # unpack
+    assert status(gf.gf_unpack_apply, csc, fake, 1024, sel_idx=fake, k=1) == E             # nowhere to write
+    assert status(gf.gf_unpack_apply, csc, fake, 1025, sel_idx=fake, k=1, out_pool=fake) == E
+    assert status(gf.gf_unpack_apply, csc, fake, 1024, sel_idx=fake, k=2, out_pool=fake) == E
+    assert status(gf.gf_unpack_apply, dense, fake, 8192, reduced_l1=fake, out_pool=fake) == E
+    assert status(gf.gf_unpack_apply, dense, fake, 8000, out_pool=fake) == E
+    assert status(gf.gf_unpack_apply, csc, fake, 2000, sel_idx=fake, k=2, out_pool=fake) == S

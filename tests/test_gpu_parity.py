@@ -1,0 +1,440 @@
+"""GPU-vs-checker parity, stage by stage and over whole iterations, through the
+C ABI.  Bit-exact for every fp16 value, every fixed-order fp32 result and every
+index; chunk norms and scores within 1e-5 relative; a selection may differ from
+the checker's only among chunks whose scores tie with the k-th within that
+tolerance (the GPU's choice is then handed to the checker so that everything
+downstream stays bit-comparable)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import binding as ob, pipeline as op
+from paper_1902_06855_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def gfm():
+    from paper_1902_06855_amd import gf, pipeline
+    return gf, pipeline
+
+
+def bits(a: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    return a.view({2: np.uint16, 4: np.uint32, 8: np.uint64}[a.dtype.itemsize])
+
+
+def same_bits(gpu: torch.Tensor, ref: np.ndarray, what: str):
+    g = gpu.detach().cpu().numpy()
+    assert g.shape == ref.shape, f"{what}: shape {g.shape} vs {ref.shape}"
+    bad = np.flatnonzero(bits(g).ravel() != bits(ref).ravel())
+    assert bad.size == 0, f"{what}: {bad.size} of {g.size} differ, first at {bad[:5]}: " \
+                          f"gpu {g.ravel()[bad[:5]]} ref {ref.ravel()[bad[:5]]}"
+
+
+def close_rel(gpu: torch.Tensor, ref: np.ndarray, what: str, rtol=RTOL):
+    g = gpu.detach().cpu().numpy().astype(np.float64)
+    r = ref.astype(np.float64)
+    err = np.abs(g - r) / np.maximum(np.abs(r), 1e-300)
+    err[(r == 0) & (g == 0)] = 0
+    assert err.max(initial=0) <= rtol, f"{what}: max rel err {err.max()}"
+
+
+def admissible_selection(g_sel: np.ndarray, o_sel: np.ndarray, score: np.ndarray, k: int, what: str):
+    assert g_sel.shape == (k,) and np.all(np.diff(g_sel) > 0), f"{what}: not k ascending indices"
+    if np.array_equal(g_sel, o_sel):
+        return
+    kth = np.sort(score)[::-1][k - 1]
+    for c in np.setxor1d(g_sel, o_sel):
+        assert abs(score[c] - kth) <= RTOL * abs(kth), f"{what}: chunk {c} differs and is not tied with the k-th"
+
+
+def cpu_grads(w, t):
+    return wl.gradients(w, t, device="cpu")
+
+
+def to_dev(grads):
+    return [[x.cuda() for x in row] for row in grads]
+
+
+def pools_np(grads, sizes):
+    return np.stack([op.fuse([x.numpy() for x in row], sizes) for row in grads])
+
+
+def odd_workload(P=3, chunk=96, wire="f16", S=64.0, density=0.3):
+    # odd sizes: tensors start at unaligned pool offsets -> scalar paths, ragged tails
+    return wl.Workload("odd", [50, 7, 701, 33, 1201, 64, 5, 4099], P=P, chunk=chunk, density=density,
+                       loss_scale=S, theta=1000, wire=wire)
+
+
+# ------------------------------------------------------------------ ring alone
+
+def _halves(rng, P, L, special=True):
+    x = (rng.standard_normal((P, L)) * 2.0 ** rng.integers(-16, 14, size=(P, 1))).astype(np.float16)
+    u = x.view(np.uint16).copy()
+    if special and L >= 64:
+        u[:, 0:8] = rng.integers(0, 0x0400, size=(P, 8))            # subnormals
+        u[:, 8:16] = 0x7bff                                          # max finite -> overflow to inf
+        u[0, 16:24] = 0x8000                                         # -0
+        u[:, 24:32] = rng.integers(0x7800, 0x7c00, size=(P, 8))      # large
+    return u
+
+
+@pytest.mark.parametrize("P,L", [(1, 100), (2, 4096), (3, 1000), (4, 253952), (8, 100003), (16, 65536),
+                                 (64, 262144), (5, 7), (8, 8)])
+def test_ring_single_bucket_bit_exact(gfm, P, L):
+    gf, _ = gfm
+    rng = np.random.default_rng(P * 7 + L)
+    C = 1024
+    nch = -(-L // C)
+    plan = gf.Plan([nch * C], 1 << 40, C, P)
+    x = _halves(rng, P, L)
+    want = ob.ring_fold(x, "f16")
+    send = [torch.from_numpy(x[p].view(np.float16)).cuda() for p in range(P)]
+    tab = gf.ptr_table(send)
+    red = torch.zeros(L, dtype=torch.float16, device="cuda")
+    ag = [torch.zeros(L, dtype=torch.float16, device="cuda") for _ in range(P)]
+    gf.gf_ring_reduce_sim(plan, tab, L, red, allgather_out=gf.ptr_table(ag))
+    torch.cuda.synchronize()
+    same_bits(red.view(torch.int16), want.view(np.int16), f"ring P={P} L={L}")
+    for r in range(P):                       # every rank ends with the same buffer (all-gather)
+        same_bits(ag[r].view(torch.int16), want.view(np.int16), f"allgather rank {r}")
+    # the length may also come from device memory, with L only an upper bound
+    cap = nch * C
+    send2 = [torch.zeros(cap, dtype=torch.float16, device="cuda") for _ in range(P)]
+    for p in range(P):
+        send2[p][:L] = send[p]
+    red2 = torch.full((cap,), 7.0, dtype=torch.float16, device="cuda")
+    L_dev = torch.tensor([L], dtype=torch.int64, device="cuda")
+    gf.gf_ring_reduce_sim(plan, gf.ptr_table(send2), cap, red2, L_dev=L_dev)
+    torch.cuda.synchronize()
+    same_bits(red2[:L].view(torch.int16), want.view(np.int16), "ring with device-side length")
+    assert torch.all(red2[L:] == 7.0)        # nothing past the real length is touched
+
+
+def test_ring_unaligned_buffers_and_fp32_wire(gfm):
+    gf, _ = gfm
+    rng = np.random.default_rng(3)
+    P, L = 4, 5001
+    plan = gf.Plan([8192], 1 << 40, 8192, P)
+    x = _halves(rng, P, L)
+    want = ob.ring_fold(x, "f16")
+    raw = [torch.zeros(L + 8, dtype=torch.float16, device="cuda") for _ in range(P)]
+    send = [raw[p][1 + p % 2:1 + p % 2 + L] for p in range(P)]       # 2-byte aligned only
+    for p in range(P):
+        send[p].copy_(torch.from_numpy(x[p].view(np.float16)))
+    red = torch.zeros(L + 3, dtype=torch.float16, device="cuda")[3:]
+    gf.gf_ring_reduce_sim(plan, gf.ptr_table(send), L, red)
+    torch.cuda.synchronize()
+    same_bits(red.view(torch.int16), want.view(np.int16), "unaligned ring")
+
+    plan32 = gf.Plan([8192], 1 << 40, 8192, P, wire=gf.GF_WIRE_F32)
+    y = (rng.standard_normal((P, L)) * 10.0 ** rng.integers(-6, 6, size=(P, 1))).astype(np.float32)
+    want32 = ob.ring_fold(y, "f32")
+    send32 = [torch.from_numpy(y[p]).cuda() for p in range(P)]
+    red32 = torch.zeros(L, dtype=torch.float32, device="cuda")
+    gf.gf_ring_reduce_sim(plan32, gf.ptr_table(send32), L, red32)
+    torch.cuda.synchronize()
+    same_bits(red32, want32, "fp32 ring")
+
+
+# ------------------------------------------------------------------ dense path
+
+def _run_dense(gfm, w, mode, S=None, scatter=True):
+    gf, pl = gfm
+    S = S or w.loss_scale
+    grads = cpu_grads(w, 0)
+    pools = pools_np(grads, w.sizes)
+    ref = op.dense_iteration(pools, w.sizes, w.theta, S, w.wire)
+    pipe = pl.Pipeline(w.sizes, w.P, 0, w.theta, S, wire=w.wire, scatter_out=scatter, allgather=True)
+    if mode == "gather":
+        pipe.set_gradients(to_dev(grads))
+    else:
+        pipe.set_pools([torch.from_numpy(pools[p]).cuda() for p in range(w.P)])
+    pipe.out_pool.fill_(-77.0)
+    pipe.cast_dense()
+    torch.cuda.synchronize()
+    for p in range(w.P):
+        same_bits(pipe.send[p].view(torch.int16 if w.wire == "f16" else torch.int32),
+                  ref["send"][p].view(np.int16 if w.wire == "f16" else np.int32), f"send[{p}]")
+    pipe.ring()
+    torch.cuda.synchronize()
+    it = torch.int16 if w.wire == "f16" else torch.int32
+    nt = np.int16 if w.wire == "f16" else np.int32
+    same_bits(pipe.reduced.view(it), ref["reduced"].view(nt), "reduced")
+    same_bits(pipe.ag[w.P - 1].view(it), ref["reduced"].view(nt), "allgather copy")
+    pipe.unpack()
+    torch.cuda.synchronize()
+    same_bits(pipe.out_pool, ref["out"], "out pool")
+    if scatter:
+        for j, v in enumerate(op.views(ref["out"], w.sizes)):
+            same_bits(pipe.out_tensors[j], np.ascontiguousarray(v), f"out tensor {j}")
+    return pipe
+
+
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+def test_dense_odd_sizes_many_buckets(gfm, mode, wire):
+    w = odd_workload(P=3, chunk=0, wire=wire)
+    pipe = _run_dense(gfm, w, mode)
+    assert pipe.plan.n_buckets > 1
+
+
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+def test_dense_resnet_shaped_scaled(gfm, mode):
+    w = wl.scaled(wl.config("resnet50_dense_4mb"), 16)
+    pipe = _run_dense(gfm, w, mode)
+    assert pipe.plan.n_buckets >= 8
+
+
+def test_dense_alexnet_shaped_scaled_P8(gfm):
+    _run_dense(gfm, wl.scaled(wl.config("alexnet_dense"), 32), "gather")
+
+
+def test_dense_loss_scale_that_is_not_a_power_of_two(gfm):
+    # acc * S is then inexact in fp32 and rounded again to fp16: both roundings must happen
+    w = wl.Workload("np2", [1 << 20], P=2, chunk=0, density=1.0, loss_scale=1000.0, theta=1 << 40)
+    _run_dense(gfm, w, "gather", scatter=False)
+
+
+def test_cast_rounding_boundaries(gfm):
+    """Every tie and near-tie between neighbouring halves, subnormals, overflow, signed zero."""
+    gf, pl = gfm
+    h = np.arange(0, 0x7c00, dtype=np.uint16)
+    lo = h.view(np.float16).astype(np.float64)
+    hi = (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    hi[-1] = 65536.0
+    mid = ((lo + hi) / 2).astype(np.float32)
+    vals = np.concatenate([mid, np.nextafter(mid, np.float32(-np.inf)), np.nextafter(mid, np.float32(np.inf)),
+                           lo.astype(np.float32),
+                           np.array([0.0, -0.0, 1e-40, -1e-40, 65519.99, 65520.0, 1e9, np.inf, -np.inf],
+                                    dtype=np.float32)])
+    vals = np.concatenate([vals, -vals]).astype(np.float32)
+    n = vals.size
+    pipe = pl.Pipeline([n], 1, 0, 1 << 40, 1.0)
+    g = torch.from_numpy(vals).cuda()
+    pipe.set_gradients([[g]])
+    pipe.cast_dense()
+    torch.cuda.synchronize()
+    same_bits(pipe.send[0].view(torch.int16), ob.f32_to_f16(vals).view(np.int16), "fp32->fp16 boundaries")
+    # fp16 -> fp32 of every half (unpack with alpha = 1)
+    allh = np.arange(65536, dtype=np.uint16)
+    fin = ~np.isnan(allh.view(np.float16))
+    allh = allh[fin]
+    pipe2 = pl.Pipeline([allh.size], 1, 0, 1 << 40, 1.0)
+    pipe2.reduced.copy_(torch.from_numpy(allh.view(np.float16)).cuda())
+    pipe2.unpack()
+    torch.cuda.synchronize()
+    same_bits(pipe2.out_pool, ob.f16_to_f32(allh), "fp16->fp32 all halves")
+    # fp32 subnormal products: loss scaling lifts them into half's range
+    tiny = (np.arange(1, 4097, dtype=np.float64) * 2.0 ** -140).astype(np.float32)
+    pipe3 = pl.Pipeline([tiny.size], 1, 0, 1 << 40, 2.0 ** 120)
+    pipe3.set_gradients([[torch.from_numpy(tiny).cuda()]])
+    pipe3.cast_dense()
+    torch.cuda.synchronize()
+    same_bits(pipe3.send[0].view(torch.int16), ob.cast_dense(tiny[None, :], 2.0 ** 120)[0].view(np.int16),
+              "subnormal inputs")
+
+
+# -------------------------------------------------------------------- selection
+
+@pytest.mark.parametrize("nc,k", [(1, 1), (5, 1), (5, 5), (245, 62), (1861, 187), (3120, 32), (50_000, 777),
+                                  (2049, 1024)])
+def test_select_bit_exact_including_ties(gfm, nc, k):
+    gf, _ = gfm
+    rng = np.random.default_rng(nc + k)
+    P, C = 3, 8
+    plan = gf.Plan([nc * C - 3], 1 << 40, C, P)
+    l1 = rng.random((P, nc)).astype(np.float32)
+    dup = rng.integers(0, nc, size=max(1, nc // 4))
+    l1[:, dup] = l1[:, dup[0]][:, None]                   # exact ties, possibly at the threshold
+    if nc > 100:
+        l1[:, 10:40] = 0                                  # a run of zeros
+    sc = ob.score(l1)
+    want, wmask = ob.select(sc, k)
+    d_l1 = torch.from_numpy(l1).cuda().reshape(-1)
+    scores = torch.zeros(nc, dtype=torch.float32, device="cuda")
+    sel = torch.zeros(k, dtype=torch.int32, device="cuda")
+    mask = torch.zeros(nc, dtype=torch.uint8, device="cuda")
+    plen = torch.zeros(1, dtype=torch.int64, device="cuda")
+    gf.gf_chunk_score_select(plan, d_l1, k=k, scores=scores, sel_idx=sel, mask=mask, packed_len=plen,
+                             workspace=plan.workspace())
+    torch.cuda.synchronize()
+    same_bits(scores, sc, "scores")
+    assert np.array_equal(sel.cpu().numpy(), want)
+    assert np.array_equal(mask.cpu().numpy(), wmask)
+    assert int(plen.item()) == ob.packed_len(nc * C - 3, C, want)
+    # all-equal scores: the lowest indices win
+    d_l1.fill_(1.0)
+    gf.gf_chunk_score_select(plan, d_l1, k=k, sel_idx=sel, workspace=plan.workspace())
+    torch.cuda.synchronize()
+    assert np.array_equal(sel.cpu().numpy(), np.arange(k))
+
+
+def test_select_after_allreduce_scores_sent_chunks_by_their_reduced_norm(gfm):
+    gf, _ = gfm
+    rng = np.random.default_rng(8)
+    P, nc, k, C = 6, 500, 50, 16
+    plan = gf.Plan([nc * C], 1 << 40, C, P)
+    l1 = rng.random((P, nc)).astype(np.float32)
+    prev = np.sort(rng.choice(nc, size=k, replace=False)).astype(np.int32)
+    red = (rng.random(k) * 5).astype(np.float32)
+    sc = ob.score(l1, prev, red)
+    want, _ = ob.select(sc, k)
+    scores = torch.zeros(nc, dtype=torch.float32, device="cuda")
+    sel = torch.from_numpy(prev).cuda()                   # output overwrites the previous selection
+    gf.gf_chunk_score_select(plan, torch.from_numpy(l1).cuda().reshape(-1), reduced_l1=torch.from_numpy(red).cuda(),
+                             prev_sel=sel, k_prev=k, k=k, scores=scores, sel_idx=sel, workspace=plan.workspace())
+    torch.cuda.synchronize()
+    same_bits(scores, sc, "scores with sent chunks")
+    assert np.array_equal(sel.cpu().numpy(), want)
+
+
+# ------------------------------------------------- sparse path, stage by stage
+
+def _run_csc(gfm, w, schedule, mode, T, k=None, scatter=False):
+    gf, pl = gfm
+    nc = ob.n_chunks(w.N, w.chunk)
+    k = k or w.k_for(nc)
+    pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=k, mu=w.mu, wire=w.wire,
+                       schedule=schedule, scatter_out=scatter)
+    assert pipe.n_chunks == nc
+    st = op.new_state(w.P, w.N)
+    it = torch.int16 if w.wire == "f16" else torch.int32
+    nt = np.int16 if w.wire == "f16" else np.int32
+    alpha = np.float32(1.0) / np.float32(w.loss_scale)
+    sel_now = None                                        # lagged: chosen at the end of the previous iteration
+    sync = torch.cuda.synchronize
+    for t in range(T):
+        grads = cpu_grads(w, t)
+        pools = pools_np(grads, w.sizes)
+        if mode == "gather":
+            pipe.set_gradients(to_dev(grads))
+        else:
+            pipe.set_pools([torch.from_numpy(pools[p]).cuda() for p in range(w.P)])
+        acc = ob.accumulate(pools, st.hg)
+        l1 = ob.chunk_l1(acc, w.chunk)
+        two_pass = schedule == "immediate" or t == 0
+        if two_pass:
+            pipe.accum(); sync()
+            for p in range(w.P):
+                same_bits(pipe.residual[p], acc[p], f"t={t} acc[{p}]")
+            close_rel(pipe.l1, l1.reshape(-1), f"t={t} chunk norms")
+            pipe.select(False); sync()
+            sc = ob.score(l1)
+            close_rel(pipe.scores, sc, f"t={t} scores")
+            o_sel, _ = ob.select(sc, k)
+            sel_now = pipe.sel.cpu().numpy().copy()
+            admissible_selection(sel_now, o_sel, sc, k, f"t={t} selection")
+            assert np.array_equal(np.flatnonzero(pipe.mask.cpu().numpy()), sel_now)
+            pipe.pack(); sync()
+        else:
+            assert np.array_equal(pipe.sel.cpu().numpy(), sel_now)
+            pipe.fused(); sync()
+            close_rel(pipe.l1, l1.reshape(-1), f"t={t} chunk norms (fused)")
+        L = ob.packed_len(w.N, w.chunk, sel_now)
+        assert int(pipe.packed_len.item()) == L
+        send, hg = ob.pack_residual(acc, w.chunk, sel_now, w.loss_scale, w.mu, w.wire)
+        for p in range(w.P):
+            same_bits(pipe.send[p][:L].view(it), send[p].view(nt), f"t={t} send[{p}]")
+            same_bits(pipe.residual[p], hg[p], f"t={t} hg[{p}]")
+        st.hg = hg
+        reduced = ob.ring_fold(send, w.wire)
+        pipe.ring(); sync()
+        same_bits(pipe.reduced[:L].view(it), reduced.view(nt), f"t={t} reduced")
+        out = np.full(w.N, np.float32(-5.0))
+        pipe.out_pool.fill_(-5.0)
+        red_l1 = ob.unpack(reduced, w.N, w.chunk, sel_now, alpha, out, w.wire)
+        if scatter:
+            for ot in pipe.out_tensors:
+                ot.zero_()
+        pipe.unpack(); sync()
+        same_bits(pipe.out_pool, out, f"t={t} out")
+        close_rel(pipe.red_l1, red_l1, f"t={t} reduced norms")
+        if scatter:
+            outs = op.views(out, w.sizes)
+            m = np.zeros(w.N, dtype=bool)
+            for c in sel_now:
+                m[c * w.chunk:(c + 1) * w.chunk] = True
+            for j, v in enumerate(op.views(m, w.sizes)):
+                got = pipe.out_tensors[j].cpu().numpy()
+                assert np.array_equal(bits(got[v]), bits(np.ascontiguousarray(outs[j][v]))), f"scatter tensor {j}"
+                assert np.all(got[~v] == 0)
+        if schedule == "lagged":
+            sc = ob.score(l1, sel_now, red_l1)
+            o_next, _ = ob.select(sc, k)
+            pipe.select(True); sync()
+            close_rel(pipe.scores, sc, f"t={t} scores after allreduce")
+            nxt = pipe.sel.cpu().numpy().copy()
+            admissible_selection(nxt, o_next, sc, k, f"t={t} next selection")
+            sel_now = nxt
+    return pipe
+
+
+@pytest.mark.parametrize("schedule", ["immediate", "lagged"])
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+def test_tiny_configuration(gfm, schedule, mode):
+    # P=4, six tensors, C=4096, 25 % of 245 chunks, S=1024
+    w = wl.config("tiny")
+    pipe = _run_csc(gfm, w, schedule, mode, T=2 if schedule == "lagged" else 1)
+    assert pipe.k == 62 and pipe.n_chunks == 245
+
+
+@pytest.mark.parametrize("schedule", ["immediate", "lagged"])
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+def test_csc_odd_sizes_scalar_paths(gfm, schedule, wire):
+    _run_csc(gfm, odd_workload(P=3, chunk=96, wire=wire), schedule, "gather", T=3, scatter=True)
+    _run_csc(gfm, odd_workload(P=2, chunk=1000, wire=wire), schedule, "pool", T=2)
+
+
+@pytest.mark.parametrize("schedule", ["immediate", "lagged"])
+def test_csc_momentum_below_one(gfm, schedule):
+    w = odd_workload(P=3, chunk=128)
+    w.mu = 0.9
+    _run_csc(gfm, w, schedule, "gather", T=3)
+    w2 = wl.scaled(wl.config("tiny"), 4)
+    w2.mu = 0.5
+    _run_csc(gfm, w2, schedule, "pool", T=3)
+
+
+def test_csc_every_chunk_selected_equals_dense(gfm):
+    gf, pl = gfm
+    w = odd_workload(P=4, chunk=100, density=1.0)
+    pipe = _run_csc(gfm, w, "immediate", "gather", T=2)
+    assert all(torch.all(r == 0) for r in pipe.residual)
+    grads = cpu_grads(w, 1)
+    d = op.dense_iteration(pools_np(grads, w.sizes), w.sizes, 1 << 40, w.loss_scale)
+    # (the second iteration starts from a zero residual, so it is a dense iteration)
+    same_bits(pipe.out_pool, d["out"], "k = n_chunks vs dense")
+
+
+def test_alexnet_csc_scaled_all_iterations(gfm):
+    w = wl.scaled(wl.config("alexnet_csc"), 16)          # P=16, 10 iterations
+    _run_csc(gfm, w, "lagged", "gather", T=w.iterations)
+
+
+def test_resnet50_csc_scaled_all_iterations(gfm):
+    w = wl.scaled(wl.config("resnet50_csc"), 32)         # P=64, 161 tensors, 20 iterations
+    _run_csc(gfm, w, "lagged", "gather", T=w.iterations)
+
+
+def test_step_runs_the_same_sequence(gfm):
+    """Pipeline.step() (what the benchmark times) against the stage-by-stage run."""
+    gf, pl = gfm
+    w = wl.scaled(wl.config("tiny"), 2)
+    nc = ob.n_chunks(w.N, w.chunk)
+    k = w.k_for(nc)
+    for schedule in ("lagged", "immediate"):
+        a = _run_csc(gfm, w, schedule, "gather", T=4)
+        b = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=k, schedule=schedule)
+        for t in range(4):
+            b.set_gradients(to_dev(cpu_grads(w, t)))
+            b.out_pool.fill_(-5.0)
+            b.step()
+        torch.cuda.synchronize()
+        assert torch.equal(a.out_pool, b.out_pool) and torch.equal(a.sel, b.sel)
+        for p in range(w.P):
+            assert torch.equal(a.residual[p], b.residual[p])
