@@ -32,8 +32,21 @@ typedef uint32_t gf_u32x4 __attribute__((ext_vector_type(4)));
 // to nearest even and keep subnormals under the default float mode of HIP
 // kernels (no flush-to-zero is requested anywhere in this library).
 
+// Plain conversion.  The compiler may merge it with the arithmetic that made x
+// (for the sum of two halves that is the exact native half add).
+__device__ __forceinline__ uint16_t gf_f32_to_h_mergeable(float x)
+{
+    const _Float16 h = static_cast<_Float16>(x);
+    return __builtin_bit_cast(uint16_t, h);
+}
+
 __device__ __forceinline__ uint16_t gf_f32_to_h(float x)
 {
+    // The empty asm keeps the conversion an instruction of its own.  Folded into
+    // a preceding fp32 multiply (the mixed-precision fma) the exact product
+    // would be rounded once, straight to fp16; the value that travels is the
+    // fp32 product, rounded, then converted (two roundings, like any fp32 value).
+    asm("" : "+v"(x));
     const _Float16 h = static_cast<_Float16>(x);
     return __builtin_bit_cast(uint16_t, h);
 }
@@ -45,16 +58,19 @@ __device__ __forceinline__ float gf_h_to_f32(uint16_t b)
 
 // One ring hop on a pair of halves packed in a 32-bit word: fp32 sum rounded
 // back to half (Section 2.5: the message is fp16, so every partial sum is).
+// 24 >= 2*11 + 2 significand bits make the two roundings equal to one, so the
+// native half add the compiler may pick instead gives the same bits.
 __device__ __forceinline__ uint32_t gf_hop_add_h2(uint32_t a, uint32_t b)
 {
     const float s0 = gf_h_to_f32(static_cast<uint16_t>(a)) + gf_h_to_f32(static_cast<uint16_t>(b));
     const float s1 = gf_h_to_f32(static_cast<uint16_t>(a >> 16)) + gf_h_to_f32(static_cast<uint16_t>(b >> 16));
-    return static_cast<uint32_t>(gf_f32_to_h(s0)) | (static_cast<uint32_t>(gf_f32_to_h(s1)) << 16);
+    return static_cast<uint32_t>(gf_f32_to_h_mergeable(s0)) |
+           (static_cast<uint32_t>(gf_f32_to_h_mergeable(s1)) << 16);
 }
 
 __device__ __forceinline__ uint16_t gf_hop_add(uint16_t a, uint16_t b)
 {
-    return gf_f32_to_h(gf_h_to_f32(a) + gf_h_to_f32(b));
+    return gf_f32_to_h_mergeable(gf_h_to_f32(a) + gf_h_to_f32(b));
 }
 
 __device__ __forceinline__ float gf_hop_add(float a, float b) { return a + b; }
