@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Throughput of the gradient-aggregation path on one MI355X.
+
+A "step" is one whole iteration of the path over one batch of synthetic
+gradients for all P simulated workers: fuse + accumulate + chunk norms + pack +
+historical-gradient rule (gf_fuse_pack), ring reduce (gf_ring_reduce_sim),
+unpack (gf_unpack_apply) and scoring / selection for the next iteration
+(gf_chunk_score_select).  All inputs are resident in HBM before the timed
+region.  The metric is algorithmic bytes per step / time per step (GB/s) and
+its share of the 8 TB/s HBM peak.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel, timed with
+events on the launch stream inside the timed region; `cpu_baseline` is the CPU
+checker run on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
+# profiles/.  Keyed by workload; absent -> null in the JSON.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(w, k_elems_L: int, schedule: str):
+    """Bytes the method must move per iteration (every gradient read once, the
+    historical gradient read and written once, each wire element written once
+    and read once per worker, the reduced buffer written once and read once,
+    each output written once).  Returns (total, per-stage dict)."""
+    P, N, L = w.P, w.N, k_elems_L
+    ws = 2 if w.wire == "f16" else 4
+    if w.chunk == 0:
+        st = {"cast": P * N * (4 + ws), "ring": N * (P * ws + ws), "unpack": N * (ws + 4)}
+    elif schedule == "lagged":
+        st = {"fused": P * N * 12 + P * L * ws, "ring": L * (P * ws + ws), "unpack": L * (ws + 4), "select": 0}
+    else:
+        st = {"accum": P * N * 12, "pack": P * L * (4 + ws + 4), "ring": L * (P * ws + ws),
+              "unpack": L * (ws + 4), "select": 0}
+    return sum(st.values()), st
+
+
+def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int):
+    import torch
+    from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
+
+    w = wl.config(name)
+    torch.cuda.set_device(0)
+    sig = wl.sigma_table(w)
+    pipe_k = 0
+    probe_plan = gf.Plan(w.sizes, min(w.theta, 1 << 60), w.chunk, w.P, to_device=False)
+    if w.chunk:
+        pipe_k = w.k_for(probe_plan.n_chunks)
+    off, _, _ = probe_plan.layout()
+    probe_plan.close()
+    pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=pipe_k, mu=w.mu, wire=w.wire,
+                       schedule=schedule)
+    # gradient sets resident in HBM: scattered per-tensor allocations (fusion is folded into the
+    # read) or one pool per worker (the zero-copy layout)
+    tables, keep = [], []
+    t_gen = time.perf_counter()
+    for s in range(n_sets):
+        if mode == "gather":
+            g = wl.gradients(w, s, device="cuda", sig=sig)
+            keep.append(g)
+            tables.append((gf.ptr_table([t for row in g for t in row]), None))
+        else:
+            pools = []
+            for p in range(w.P):
+                pool = torch.empty(w.N, dtype=torch.float32, device="cuda")
+                for l in range(w.m):
+                    pool[off[l]:off[l] + w.sizes[l]] = wl.gradient_tensor(w, sig, s, p, l, "cuda")
+                pools.append(pool)
+            keep.append(pools)
+            tables.append((None, gf.ptr_table(pools)))
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    it = 0
+    for _ in range(warmup):
+        pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
+    torch.cuda.synchronize()
+    pipe.probe = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    probe, pipe.probe = pipe.probe, None
+
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    L = int(pipe.packed_len.item()) if w.chunk else w.N
+    total_bytes, per_stage_bytes = algorithmic_bytes(w, L, schedule)
+    stage_ms = {}
+    for nm, e0, e1 in probe:
+        stage_ms.setdefault(nm, []).append(e0.elapsed_time(e1))
+    stage_avg = {nm: sum(v) / len(v) for nm, v in stage_ms.items()}
+    dominant = max(per_stage_bytes, key=per_stage_bytes.get)
+    res = {
+        "workload": name, "P": w.P, "N": w.N, "m": w.m, "chunk": w.chunk, "k": pipe_k, "L": L,
+        "schedule": schedule if w.chunk else "dense", "input": mode, "n_buckets": pipe.plan.n_buckets,
+        "ms_per_step": ms_per_step, "bytes_per_step": total_bytes,
+        "gbs": total_bytes / ms_per_step / 1e6, "payload_gbs": w.P * w.N * 4 / ms_per_step / 1e6,
+        "elements_per_s": w.P * w.N / ms_per_step * 1e3,
+        "stage_ms": stage_avg, "stage_bytes": per_stage_bytes, "dominant": dominant,
+        "dominant_ms": stage_avg.get(dominant), "gen_s": t_gen, "steps_timed": steps,
+    }
+    del keep, tables, pipe
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(name: str, schedule: str, threads: int):
+    """The CPU checker, as it stands, on host cores: one whole steady-state iteration of the same
+    workload with the worker count cut down so that the run stays bounded.  Timed twice on the
+    same inputs: with `threads` OpenMP threads (the reported value) and with one."""
+    import numpy as np
+    from oracle import binding as ob, pipeline as op
+    from paper_1902_06855_amd import workloads as wl
+
+    w = wl.config(name)
+    P_s = min(w.P, 4)                      # sample: the first P_s workers, every tensor, full size
+    ws = wl.Workload(w.name + "_sample", w.sizes, P_s, w.chunk, w.density, w.loss_scale, w.theta,
+                     w.iterations, w.mu, w.seed, w.wire)
+    sig = wl.sigma_table(w)[:, :P_s]
+    pools = []
+    for t in range(2):
+        g = [[wl.gradient_tensor(w, sig, t, p, l, "cpu").numpy() for l in range(w.m)] for p in range(P_s)]
+        pools.append(np.stack([op.fuse(row, w.sizes) for row in g]))
+        del g
+
+    def once(nthreads):
+        ob.set_threads(nthreads)
+        used = ob.get_threads()
+        if w.chunk:
+            k = w.k_for(ob.n_chunks(w.N, w.chunk))
+            state = op.new_state(P_s, w.N)
+            op.csc_iteration(state, pools[0], w.chunk, k, w.loss_scale, w.mu, schedule, w.wire)   # iteration 0
+            t0 = time.perf_counter()
+            r = op.csc_iteration(state, pools[1], w.chunk, k, w.loss_scale, w.mu, schedule, w.wire)
+            dt = time.perf_counter() - t0
+            L = r["send"].shape[1]
+        else:
+            t0 = time.perf_counter()
+            op.dense_iteration(pools[1], w.sizes, w.theta, w.loss_scale, w.wire)
+            dt = time.perf_counter() - t0
+            L = w.N
+        total_bytes, _ = algorithmic_bytes(ws, L, schedule)
+        return used, dt, total_bytes
+
+    used, dt, total_bytes = once(threads)
+    _, dt1, _ = once(1)
+    return {
+        "value": total_bytes / dt / 1e9, "unit": "GB/s", "cores": used, "kind": "oracle",
+        "sample": f"one steady-state {schedule if w.chunk else 'dense'} iteration of {name} with the first "
+                  f"{P_s} of {w.P} workers (all {w.m} tensors, full size; bytes counted for {P_s} workers)",
+        "seconds": dt, "elements_per_s": P_s * w.N / dt,
+        "single_thread_value": total_bytes / dt1 / 1e9, "single_thread_seconds": dt1,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="alexnet_csc")
+    ap.add_argument("--input", choices=["gather", "pool"], default="gather")
+    ap.add_argument("--schedule", choices=["lagged", "immediate"], default="lagged")
+    ap.add_argument("--others", default="alexnet_dense,resnet50_dense_4mb,resnet50_dense_64mb,resnet50_csc",
+                    help="comma-separated extra workloads reported under config.others ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the P workers are simulated in one GPU's HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: launched with WORLD_SIZE > 1; this build has no multi-GPU path", file=sys.stderr)
+        return 2
+    from paper_1902_06855_amd import workloads as wl
+    w = wl.config(a.workload)
+    steps = a.steps if a.steps is not None else max(10, w.iterations)
+    warmup = a.warmup if a.warmup is not None else 5
+    n_sets = min(steps, 10) if w.chunk else 2
+
+    main_res = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets)
+    others = {}
+    for nm in [x for x in a.others.split(",") if x and x != a.workload]:
+        wo = wl.config(nm)
+        so = max(10, wo.iterations)
+        r = run_gpu(nm, so, 5, a.input, a.schedule, 4 if wo.chunk else 2)
+        others[nm] = {kk: r[kk] for kk in ("P", "N", "schedule", "n_buckets", "ms_per_step", "gbs", "payload_gbs",
+                                            "stage_ms", "dominant", "dominant_ms")}
+        others[nm]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
+        dom_b = r["stage_bytes"][r["dominant"]]
+        others[nm]["dominant_gbs"] = dom_b / r["dominant_ms"] / 1e6
+
+    dom = main_res["dominant"]
+    dom_bytes = main_res["stage_bytes"][dom]
+    achieved = dom_bytes / main_res["dominant_ms"] / 1e6
+    kernel = {"fused": "k_fuse<MODE_FUSED> (gf_fuse_pack, accumulate+norms+pack+historical gradient)",
+              "cast": "k_fuse<MODE_DENSE> (gf_fuse_pack, fused gather + scale + fp16 cast)",
+              "accum": "k_fuse<MODE_ACCUM> (gf_fuse_pack, accumulate + norms)"}.get(dom, dom)
+    out = {
+        "metric": "gradient GB/s per step (fuse+sparsify+reduce) and % of MI355X HBM peak",
+        "value": main_res["gbs"], "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32->f16" if w.wire == "f16" else "f32", "data": "synthetic",
+        "frac_of_hbm_peak": main_res["gbs"] / HBM_PEAK_GBS,
+        "payload_gbs": main_res["payload_gbs"], "elements_per_s": main_res["elements_per_s"],
+        "config": {"workload": a.workload, "P": w.P, "N": w.N, "tensors": w.m, "chunk": w.chunk,
+                   "k": main_res["k"], "packed_elems": main_res["L"], "loss_scale": w.loss_scale,
+                   "schedule": main_res["schedule"], "input": a.input,
+                   "bytes_per_step": main_res["bytes_per_step"], "stage_ms": main_res["stage_ms"],
+                   "gradient_sets_resident": n_sets, "others": others},
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "bytes_per_launch": dom_bytes,
+                     "avg_launch_ms": main_res["dominant_ms"],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload)},
+    }
+    if not a.no_cpu_baseline:
+        ncpu = min(16, os.cpu_count() or 1)
+        out["cpu_baseline"] = cpu_baseline(a.workload, a.schedule, ncpu)
+        out["cpu_baseline"]["gpu_over_cpu"] = main_res["gbs"] / out["cpu_baseline"]["value"]
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -67,6 +67,7 @@ class Pipeline:
             self.ag_tab = gf.ptr_table(self.ag, device)
         self.grads_tab = self.pools_tab = None
         self._keep = None
+        self.probe = None            # list to collect (stage, start event, end event) per launch
 
     # ------------------------------------------------------------- inputs
     def set_gradients(self, grads: List[List[torch.Tensor]]) -> None:
@@ -133,14 +134,27 @@ class Pipeline:
                                out_tensors=self.out_tab, workspace=self.ws)
 
     # ---------------------------------------------------------- iteration
+    def _run(self, name: str, fn, after: bool = False) -> None:
+        """Run one stage; with a probe list attached, bracket it with events on the launch stream."""
+        if self.probe is None:
+            fn(after) if name == "select" else fn()
+            return
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn(after) if name == "select" else fn()
+        e1.record()
+        self.probe.append((name, e0, e1))
+
     def step(self) -> None:
         """One whole iteration on the current stream; returns without synchronising."""
         if not self.chunk:
-            self.cast_dense(); self.ring(); self.unpack()
+            self._run("cast", self.cast_dense); self._run("ring", self.ring); self._run("unpack", self.unpack)
         elif self.schedule == "immediate" or self.t == 0:
-            self.accum(); self.select(False); self.pack(); self.ring(); self.unpack()
+            self._run("accum", self.accum); self._run("select", self.select, False)
+            self._run("pack", self.pack); self._run("ring", self.ring); self._run("unpack", self.unpack)
             if self.schedule == "lagged":
-                self.select(True)
+                self._run("select", self.select, True)
         else:
-            self.fused(); self.ring(); self.unpack(); self.select(True)
+            self._run("fused", self.fused); self._run("ring", self.ring); self._run("unpack", self.unpack)
+            self._run("select", self.select, True)
         self.t += 1
