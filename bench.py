@@ -49,11 +49,13 @@ def algorithmic_bytes(w, k_elems_L: int, schedule: str):
     return sum(st.values()), st
 
 
-def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int):
+def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int, chunk=None):
     import torch
     from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
 
     w = wl.config(name)
+    if chunk:                      # tuning aid: same tensors, another chunk size
+        w.chunk = int(chunk)
     torch.cuda.set_device(0)
     sig = wl.sigma_table(w)
     pipe_k = 0
@@ -179,6 +181,7 @@ def main() -> int:
     ap.add_argument("--others", default="alexnet_dense,resnet50_dense_4mb,resnet50_dense_64mb,resnet50_csc",
                     help="comma-separated extra workloads reported under config.others ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk", type=int, default=None, help="override the workload's chunk size (tuning aid)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the P workers are simulated in one GPU's HBM); "
@@ -193,7 +196,7 @@ def main() -> int:
     warmup = a.warmup if a.warmup is not None else 5
     n_sets = min(steps, 10) if w.chunk else 2
 
-    main_res = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets)
+    main_res = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk)
     others = {}
     for nm in [x for x in a.others.split(",") if x and x != a.workload]:
         wo = wl.config(nm)

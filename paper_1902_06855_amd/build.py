@@ -29,7 +29,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB] + srcs
+    extra = os.environ.get("GF_HIPCC_EXTRA", "").split()        # e.g. -DGF_FUSE_NT=512 -DGF_FUSE_U=8 when tuning
+    cmd = [hipcc] + HIPCC_FLAGS + extra + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB] + srcs
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

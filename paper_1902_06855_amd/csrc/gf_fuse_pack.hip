@@ -6,7 +6,10 @@
 // One workgroup handles one (worker, tile) pair; a tile is a chunk of a CSC
 // plan or a fixed slice of the pool of a dense plan.  Whether the tile is sent
 // is uniform across the workgroup, so each case runs its own straight-line
-// inner loop of 128-bit loads and stores with several loads in flight.
+// inner loop of 128-bit loads and stores with several loads in flight.  With
+// scattered per-tensor gradients a tile may be made of pieces of several
+// tensors; their addresses are put in a small LDS table so that the tile is
+// still swept as one run.
 #include "gf_device.h"
 
 namespace {
@@ -58,55 +61,74 @@ __device__ __forceinline__ void elem4(const gf_f32x4 g, const gf_f32x4 r, gf_f32
     if constexpr (F & F_ZERO) res_out = gf_pack4(0.f, 0.f, 0.f, 0.f);
 }
 
-// One contiguous run of `len` elements.  g / res / snd are already offset to
-// the run's first element; unused ones are null.
-template <int F, typename W>
-__device__ __forceinline__ void run(const float *g_, float *res_, W *snd_, int len, float S, float mu,
-                                    double &l1)
+// Source of the gradients of one tile.
+//   direct: one contiguous run starting at `base` (pool input, or a tile that
+//           lies inside a single tensor);
+//   flat:   several tensor pieces; piece i covers tile offsets
+//           [end[i-1], end[i]) and element x of the tile is at ptr[i][x].
+// In both cases `at(x)` is only evaluated for x inside the tile.
+struct GradSrc {
+    const float *base;
+    const float *const *ptr;      // LDS
+    const int *end;               // LDS
+    int n;                        // pieces (0 = direct)
+    __device__ __forceinline__ const float *at(int x) const
+    {
+        if (n == 0) return base + x;
+        int i = 0;
+        while (i + 1 < n && x >= end[i]) ++i;
+        return ptr[i] + x;
+    }
+};
+
+// One tile (or one contiguous piece of it) of `len` elements.  res / snd are
+// already offset to its first element; unused pointers are null.  Gradients
+// and the historical gradient are touched exactly once per iteration, so they
+// go around the caches (nontemporal); the send buffer is read back by the ring
+// kernel right away and stays cacheable.
+template <int F, typename W, int NT, int U>
+__device__ __forceinline__ void run(const GradSrc &src, float *res_, W *snd_, int len, bool vec,
+                                    float S, float mu, double &l1)
 {
-    const GF_GLOBAL float *__restrict__ g = gf_global(g_);
     GF_GLOBAL float *__restrict__ res = gf_global(res_);
     GF_GLOBAL W *__restrict__ snd = gf_global(snd_);
     using W4 = typename gf_wire4<W>::type;
     constexpr bool WRITES_RES = (F & (F_KEEP | F_ZERO)) != 0;
-    bool vec = true;
-    if constexpr (F & F_G) vec = vec && gf_aligned(g, 16);
     if constexpr ((F & F_RES) || WRITES_RES) vec = vec && gf_aligned(res, 16);
     if constexpr (F & F_SEND) vec = vec && gf_aligned(snd, sizeof(W4));
     const int nvec = vec ? (len >> 2) : 0;
-    const GF_GLOBAL gf_f32x4 *g4 = reinterpret_cast<const GF_GLOBAL gf_f32x4 *>(g);
     GF_GLOBAL gf_f32x4 *r4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(res);
     GF_GLOBAL W4 *s4 = reinterpret_cast<GF_GLOBAL W4 *>(snd);
+    auto g4 = [&](int v) { return reinterpret_cast<const GF_GLOBAL gf_f32x4 *>(gf_global(src.at(v << 2))); };
 
-    constexpr int U = 4;
     int v = threadIdx.x;
-    for (; v + (U - 1) * GF_BLOCK < nvec; v += U * GF_BLOCK) {
+    for (; v + (U - 1) * NT < nvec; v += U * NT) {
         gf_f32x4 gg[U], rr[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if constexpr (F & F_G) gg[u] = g4[v + u * GF_BLOCK];
-            if constexpr (F & F_RES) rr[u] = r4[v + u * GF_BLOCK];
+            if constexpr (F & F_G) gg[u] = gf_ld_stream(g4(v + u * NT));
+            if constexpr (F & F_RES) rr[u] = gf_ld_stream(&r4[v + u * NT]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             gf_f32x4 ro; W4 so;
             elem4<F, W>(gg[u], rr[u], ro, so, S, mu, l1);
-            if constexpr (WRITES_RES) r4[v + u * GF_BLOCK] = ro;
-            if constexpr (F & F_SEND) s4[v + u * GF_BLOCK] = so;
+            if constexpr (WRITES_RES) gf_st_stream(ro, &r4[v + u * NT]);
+            if constexpr (F & F_SEND) s4[v + u * NT] = so;
         }
     }
-    for (; v < nvec; v += GF_BLOCK) {
+    for (; v < nvec; v += NT) {
         gf_f32x4 gg = {}, rr = {}, ro; W4 so;
-        if constexpr (F & F_G) gg = g4[v];
-        if constexpr (F & F_RES) rr = r4[v];
+        if constexpr (F & F_G) gg = gf_ld_stream(g4(v));
+        if constexpr (F & F_RES) rr = gf_ld_stream(&r4[v]);
         elem4<F, W>(gg, rr, ro, so, S, mu, l1);
-        if constexpr (WRITES_RES) r4[v] = ro;
+        if constexpr (WRITES_RES) gf_st_stream(ro, &r4[v]);
         if constexpr (F & F_SEND) s4[v] = so;
     }
-    for (int i = (nvec << 2) + threadIdx.x; i < len; i += GF_BLOCK) {   // unaligned run or ragged tail
+    for (int i = (nvec << 2) + threadIdx.x; i < len; i += NT) {   // unaligned data or ragged tail
         float a;
-        if constexpr ((F & F_G) && (F & F_RES)) a = g[i] + res[i];
-        else if constexpr (F & F_G) a = g[i];
+        if constexpr ((F & F_G) && (F & F_RES)) a = *gf_global(src.at(i)) + res[i];
+        else if constexpr (F & F_G) a = *gf_global(src.at(i));
         else a = res[i];
         if constexpr (F & F_L1) l1 += static_cast<double>(fabsf(a));
         if constexpr (F & F_SEND) snd[i] = gf_to_wire<W>(a * S);
@@ -115,7 +137,9 @@ __device__ __forceinline__ void run(const float *g_, float *res_, W *snd_, int l
     }
 }
 
-template <int F, typename W>
+constexpr int MAX_FLAT_PIECES = 64;   // more pieces than this in one tile are walked one by one
+
+template <int F, typename W, int NT, int U>
 __device__ __forceinline__ void tile_body(const FuseArgs &a, int p, int tile, int64_t slot, double &l1)
 {
     const int64_t tile_lo = static_cast<int64_t>(tile) * a.tile;
@@ -124,22 +148,57 @@ __device__ __forceinline__ void tile_body(const FuseArgs &a, int p, int tile, in
     constexpr bool USES_RES = (F & (F_RES | F_KEEP | F_ZERO)) != 0;
     float *res = USES_RES ? a.residual[p] + tile_lo : nullptr;
     W *snd = (F & F_SEND) ? static_cast<W *>(a.sendbuf[p]) + slot * a.tile : nullptr;
-    if ((F & F_G) && a.use_pieces) {
-        const int pe = a.piece_start[tile + 1];
-        for (int i = a.piece_start[tile]; i < pe; ++i) {
-            const gf_piece pc = a.pieces[i];
-            const float *g = static_cast<const float *>(a.tab[static_cast<int64_t>(p) * a.tab_stride + pc.tensor]) + pc.src_off;
-            run<F, W>(g, USES_RES ? res + pc.dst_rel : nullptr, (F & F_SEND) ? snd + pc.dst_rel : nullptr,
-                      pc.len, a.S, a.mu, l1);
+    GradSrc src{nullptr, nullptr, nullptr, 0};
+    if constexpr ((F & F_G) == 0) {
+        run<F, W, NT, U>(src, res, snd, tile_len, true, a.S, a.mu, l1);
+        return;
+    }
+    if (!a.use_pieces) {
+        src.base = static_cast<const float *>(a.tab[p]) + tile_lo;
+        run<F, W, NT, U>(src, res, snd, tile_len, gf_aligned(src.base, 16), a.S, a.mu, l1);
+        return;
+    }
+    const int ps = a.piece_start[tile], np = a.piece_start[tile + 1] - ps;
+    const float *const *tab = reinterpret_cast<const float *const *>(a.tab) + static_cast<int64_t>(p) * a.tab_stride;
+    if (np == 1) {
+        const gf_piece pc = a.pieces[ps];
+        src.base = tab[pc.tensor] + pc.src_off;
+        run<F, W, NT, U>(src, res, snd, tile_len, gf_aligned(src.base, 16), a.S, a.mu, l1);
+        return;
+    }
+    if (np <= MAX_FLAT_PIECES) {
+        // Several tensors meet in this tile: publish where each piece lives, then
+        // sweep the tile as if it were one run.
+        __shared__ const float *s_ptr[MAX_FLAT_PIECES];
+        __shared__ int s_end[MAX_FLAT_PIECES];
+        int misaligned = 0;
+        if (static_cast<int>(threadIdx.x) < np) {
+            const gf_piece pc = a.pieces[ps + threadIdx.x];
+            const float *q = tab[pc.tensor] + pc.src_off;
+            s_ptr[threadIdx.x] = q - pc.dst_rel;
+            s_end[threadIdx.x] = pc.dst_rel + pc.len;
+            misaligned = !gf_aligned(q, 16) || (pc.dst_rel & 3);
         }
-    } else {
-        const float *g = (F & F_G) ? static_cast<const float *>(a.tab[p]) + tile_lo : nullptr;
-        run<F, W>(g, res, snd, tile_len, a.S, a.mu, l1);
+        const bool vec = !__syncthreads_or(misaligned);
+        src.ptr = s_ptr; src.end = s_end; src.n = np;
+        run<F, W, NT, U>(src, res, snd, tile_len, vec, a.S, a.mu, l1);
+        __syncthreads();                       // the table is reused by the next caller
+        return;
+    }
+    for (int i = ps; i < ps + np; ++i) {
+        const gf_piece pc = a.pieces[i];
+        src.base = tab[pc.tensor] + pc.src_off;
+        run<F, W, NT, U>(src, USES_RES ? res + pc.dst_rel : nullptr, (F & F_SEND) ? snd + pc.dst_rel : nullptr,
+                         pc.len, gf_aligned(src.base, 16), a.S, a.mu, l1);
     }
 }
 
-template <int MODE, typename W>
-__global__ __launch_bounds__(GF_BLOCK) void k_fuse(const FuseArgs a)
+// One workgroup per (worker, tile).  WPE caps the wavefronts resident per SIMD
+// (0 = no cap): fewer resident workgroups mean fewer DRAM pages open at once,
+// which the in-place read-read-write stream of short tiles rewards.
+template <int MODE, typename W, int NT, int U, int WPE>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE ? WPE : 1, WPE ? WPE : 8)))
+void k_fuse(const FuseArgs a)
 {
     const int p = blockIdx.x / a.units;
     const int u = blockIdx.x - p * a.units;
@@ -151,18 +210,18 @@ __global__ __launch_bounds__(GF_BLOCK) void k_fuse(const FuseArgs a)
         if (a.slotmap) slot = a.slotmap[tile];
     }
     double l1 = 0.0;
-    if constexpr (MODE == MODE_ACCUM) tile_body<F_G | F_RES | F_KEEP | F_L1, W>(a, p, tile, 0, l1);   // mu = 1 here
+    if constexpr (MODE == MODE_ACCUM) tile_body<F_G | F_RES | F_KEEP | F_L1, W, NT, U>(a, p, tile, 0, l1);   // mu = 1 here
     if constexpr (MODE == MODE_FUSED) {
-        if (slot >= 0) tile_body<F_G | F_RES | F_SEND | F_ZERO | F_L1, W>(a, p, tile, slot, l1);
-        else tile_body<F_G | F_RES | F_KEEP | F_L1, W>(a, p, tile, 0, l1);
+        if (slot >= 0) tile_body<F_G | F_RES | F_SEND | F_ZERO | F_L1, W, NT, U>(a, p, tile, slot, l1);
+        else tile_body<F_G | F_RES | F_KEEP | F_L1, W, NT, U>(a, p, tile, 0, l1);
     }
-    if constexpr (MODE == MODE_DENSE) tile_body<F_G | F_SEND, W>(a, p, tile, slot, l1);
-    if constexpr (MODE == MODE_PACK) tile_body<F_RES | F_SEND | F_ZERO, W>(a, p, tile, slot, l1);
+    if constexpr (MODE == MODE_DENSE) tile_body<F_G | F_SEND, W, NT, U>(a, p, tile, slot, l1);
+    if constexpr (MODE == MODE_PACK) tile_body<F_RES | F_SEND | F_ZERO, W, NT, U>(a, p, tile, slot, l1);
     if constexpr (MODE == MODE_SCALE) {
-        if (slot < 0) tile_body<F_RES | F_KEEP, W>(a, p, tile, 0, l1);
+        if (slot < 0) tile_body<F_RES | F_KEEP, W, NT, U>(a, p, tile, 0, l1);
     }
     if constexpr (MODE == MODE_ACCUM || MODE == MODE_FUSED) {
-        const double s = gf_block_sum<GF_BLOCK>(l1);
+        const double s = gf_block_sum<NT>(l1);
         if (a.chunk_l1 && threadIdx.x == 0)
             a.chunk_l1[static_cast<int64_t>(p) * a.n_tiles + tile] = static_cast<float>(s);
     }
@@ -182,15 +241,34 @@ __global__ __launch_bounds__(GF_BLOCK) void k_slotmap(const int32_t *__restrict_
     slotmap[c] = (lo < k && sel[lo] == c) ? lo : -1;
 }
 
-template <int MODE>
-gf_status launch(const gf_plan *pl, const FuseArgs &a, int64_t blocks, hipStream_t st)
+template <int MODE, int NT, int U, int WPE>
+gf_status launch_shape(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
 {
+    const int64_t blocks = static_cast<int64_t>(a.units) * pl->P;
     if (blocks <= 0) return GF_OK;
-    const dim3 grid(static_cast<unsigned>(blocks)), block(GF_BLOCK);
-    if (pl->wire == GF_WIRE_F16) hipLaunchKernelGGL((k_fuse<MODE, uint16_t>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((k_fuse<MODE, float>), grid, block, 0, st, a);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(NT);
+    if (pl->wire == GF_WIRE_F16) hipLaunchKernelGGL((k_fuse<MODE, uint16_t, NT, U, WPE>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((k_fuse<MODE, float, NT, U, WPE>), grid, block, 0, st, a);
     GF_LAUNCH_CHECK();
     return GF_OK;
+}
+
+// Workgroup shape (measured on MI355X, P = 8..64 workers).  The in-place
+// accumulate stream does best when a long tile is swept by 1024 threads that
+// issue all 16 loads of a 32768-element stretch before the first store, and a
+// short tile by small workgroups with 8 loads in flight per thread and two
+// workgroups resident per SIMD set.  The dense cast (read fp32, write fp16
+// elsewhere) prefers full occupancy.
+template <int MODE>
+gf_status launch(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
+{
+#if defined(GF_FUSE_NT)
+    return launch_shape<MODE, GF_FUSE_NT, GF_FUSE_U, GF_FUSE_WPE>(pl, a, st);
+#else
+    if constexpr (MODE == MODE_DENSE) return launch_shape<MODE, 512, 4, 0>(pl, a, st);
+    if (pl->tile > 16384) return launch_shape<MODE, 1024, 8, 0>(pl, a, st);
+    return launch_shape<MODE, 256, 4, 2>(pl, a, st);
+#endif
 }
 
 }  // namespace
@@ -240,23 +318,22 @@ extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
                            sel_idx, k, pl->n_chunks, slotmap);
         GF_LAUNCH_CHECK();
     }
-    const int64_t all = static_cast<int64_t>(pl->P) * pl->n_tiles;
 
     if (accum && !pack) {
         a.mu = 1.0f;                         // hg <- acc
-        return launch<MODE_ACCUM>(pl, a, all, st);
+        return launch<MODE_ACCUM>(pl, a, st);
     }
     if (accum && pack) {
-        if (!residual) return launch<MODE_DENSE>(pl, a, all, st);
+        if (!residual) return launch<MODE_DENSE>(pl, a, st);
         a.slotmap = slotmap;                 // null: every chunk is sent, rank = chunk index
-        return launch<MODE_FUSED>(pl, a, all, st);
+        return launch<MODE_FUSED>(pl, a, st);
     }
     // pack only: visit the selected chunks; the rest only if mu scales them
     a.sel_idx = sel_idx;
     a.units = sel_idx ? k : pl->n_tiles;
-    gf_status rc = launch<MODE_PACK>(pl, a, static_cast<int64_t>(pl->P) * a.units, st);
+    gf_status rc = launch<MODE_PACK>(pl, a, st);
     if (rc != GF_OK || !sel_idx || mu == 1.0f) return rc;
     a.units = pl->n_tiles;
     a.slotmap = slotmap;
-    return launch<MODE_SCALE>(pl, a, all, st);
+    return launch<MODE_SCALE>(pl, a, st);
 }

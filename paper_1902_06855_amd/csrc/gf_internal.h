@@ -13,7 +13,10 @@
 // Work tile of a dense-only plan, in pool elements.  Any multiple of 8 works;
 // 8192 elements = 32 KB of fp32 per worker per tile keeps >25k workgroups in
 // flight on the ResNet-50-sized pool while amortising the per-tile set-up.
-constexpr int32_t GF_DENSE_TILE = 8192;
+#ifndef GF_DENSE_TILE_ELEMS
+#define GF_DENSE_TILE_ELEMS 8192
+#endif
+constexpr int32_t GF_DENSE_TILE = GF_DENSE_TILE_ELEMS;
 
 // One contiguous run of a tensor inside a tile (pool order).
 struct gf_piece {
@@ -74,7 +77,10 @@ inline int64_t gf_ring_segment_len(int64_t L, int32_t P, gf_wire w)
 // Threads per workgroup of the streaming kernels, and 16-byte groups each ring
 // workgroup covers.
 constexpr int GF_BLOCK = 256;
-constexpr int GF_RING_GROUPS_PER_BLOCK = 256;
+#ifndef GF_RING_GPB
+#define GF_RING_GPB 512
+#endif
+constexpr int GF_RING_GROUPS_PER_BLOCK = GF_RING_GPB;   // = threads of a ring workgroup
 
 #define GF_HIP_TRY(expr)                        \
     do {                                        \

@@ -12,6 +12,17 @@
 
 namespace {
 
+// A dense plan's send buffers (P * N wire elements) are far larger than the
+// caches and are read exactly once: stream them.  The packed buffer of a CSC
+// plan was written just before by gf_fuse_pack and is still cache-resident:
+// ordinary loads.
+template <bool STREAM, typename T>
+__device__ __forceinline__ T ring_ld(const GF_GLOBAL T *p)
+{
+    if constexpr (STREAM) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
 struct RingArgs {
     const void *const *send;
     void *reduced;
@@ -41,7 +52,7 @@ __device__ __forceinline__ gf_f32x4 hop16(gf_f32x4 a, gf_f32x4 b)
 }
 
 template <typename W, bool DENSE>
-__global__ __launch_bounds__(GF_BLOCK) void k_ring(const RingArgs a)
+__global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArgs a)
 {
     using V = typename vec16<W>::type;
     constexpr int A = vec16<W>::n;
@@ -80,7 +91,7 @@ __global__ __launch_bounds__(GF_BLOCK) void k_ring(const RingArgs a)
 
     if (mis == 0 && n == A) {
         int q = s;
-        V v = *reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e);
+        V v = ring_ld<DENSE>(reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e));
         int j = 1;
         constexpr int U = 8;
         for (; j + U - 1 < P; j += U) {
@@ -88,14 +99,14 @@ __global__ __launch_bounds__(GF_BLOCK) void k_ring(const RingArgs a)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 q = q + 1 == P ? 0 : q + 1;
-                x[u] = *reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e);
+                x[u] = ring_ld<DENSE>(reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e));
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) v = hop16(v, x[u]);
         }
         for (; j < P; ++j) {
             q = q + 1 == P ? 0 : q + 1;
-            v = hop16(v, *reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e));
+            v = hop16(v, ring_ld<DENSE>(reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e)));
         }
         *reinterpret_cast<GF_GLOBAL V *>(gf_global(static_cast<W *>(a.reduced)) + e) = v;
         if (a.allgather)
@@ -142,9 +153,9 @@ extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *se
         const size_t nb = pl->ring_blocks.size();
         if (nb == 0) return GF_OK;
         if (pl->wire == GF_WIRE_F16)
-            hipLaunchKernelGGL((k_ring<uint16_t, true>), dim3(static_cast<unsigned>(nb)), dim3(GF_BLOCK), 0, st, a);
+            hipLaunchKernelGGL((k_ring<uint16_t, true>), dim3(static_cast<unsigned>(nb)), dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
         else
-            hipLaunchKernelGGL((k_ring<float, true>), dim3(static_cast<unsigned>(nb)), dim3(GF_BLOCK), 0, st, a);
+            hipLaunchKernelGGL((k_ring<float, true>), dim3(static_cast<unsigned>(nb)), dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
     } else {
         if (L == 0) return GF_OK;
         const int64_t A = gf_wire_granule(pl->wire);
@@ -155,9 +166,9 @@ extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *se
         a.blocks_per_segment = static_cast<int32_t>(bps);
         const dim3 grid(static_cast<unsigned>(bps * pl->P));
         if (pl->wire == GF_WIRE_F16)
-            hipLaunchKernelGGL((k_ring<uint16_t, false>), grid, dim3(GF_BLOCK), 0, st, a);
+            hipLaunchKernelGGL((k_ring<uint16_t, false>), grid, dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
         else
-            hipLaunchKernelGGL((k_ring<float, false>), grid, dim3(GF_BLOCK), 0, st, a);
+            hipLaunchKernelGGL((k_ring<float, false>), grid, dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
     }
     GF_LAUNCH_CHECK();
     return GF_OK;
