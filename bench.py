@@ -182,6 +182,9 @@ def main() -> int:
                     help="comma-separated extra workloads reported under config.others ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=None, help="override the workload's chunk size (tuning aid)")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: first a plain elementwise copy of known size (2 GiB read, "
+                         "2 GiB written) that calibrates the byte counters, then a short run of the workload")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the P workers are simulated in one GPU's HBM); "
@@ -196,6 +199,18 @@ def main() -> int:
     warmup = a.warmup if a.warmup is not None else 5
     n_sets = min(steps, 10) if w.chunk else 2
 
+    if a.pmc_probe:
+        import torch
+        n = 1 << 29
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)       # reads 4n bytes, writes 4n bytes
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+        a.others, a.no_cpu_baseline = "", True
+        steps, warmup, n_sets = 3, 2, 2
     main_res = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk)
     others = {}
     for nm in [x for x in a.others.split(",") if x and x != a.workload]:
