@@ -1,0 +1,236 @@
+"""Parity at the full sizes of the measured configurations, in the launch
+configuration bench.py times (same Pipeline, scattered per-tensor gradients,
+lagged schedule).  The CPU checker cannot replay 10^9 elements in a test, so:
+
+  * sampled chunks / elements are recomputed by the checker from the same
+    gradient bits (copied from the GPU, never regenerated) and compared to the
+    bit, through every stage and two iterations (bootstrap + steady state);
+  * whole small vectors (chunk norms -> scores -> selection) are checked by
+    properties that hold at any size: scores are the checker's function of the
+    norm vector, the selected set is the checker's top-k of the score vector,
+    the packed length follows from the selection.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import binding as ob
+from paper_1902_06855_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def mods():
+    from paper_1902_06855_amd import gf, pipeline
+    return gf, pipeline
+
+
+def u32(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def u16(a):
+    return np.ascontiguousarray(a).view(np.uint16)
+
+
+def pool_of(grads_p):
+    """One worker's tensors laid end to end in generation order (test plumbing to cut samples)."""
+    return torch.cat([t for t in reversed(grads_p)])
+
+
+def fold_in_ring_order(cols: np.ndarray, seg_index: np.ndarray) -> np.ndarray:
+    """cols [P, n] wire halves (uint16); element i starts at worker seg_index[i] and walks up the
+    ring.  Each hop is the checker's two-rank ring (= one rounded half addition)."""
+    P, n = cols.shape
+    out = np.empty(n, dtype=np.uint16)
+    for s in np.unique(seg_index):
+        m = seg_index == s
+        v = cols[s, m].copy()
+        for j in range(1, P):
+            v = ob.ring_fold(np.stack([v, cols[(s + j) % P, m]]), "f16")
+        out[m] = v
+    return out
+
+
+# ------------------------------------------------------------------- dense
+
+@pytest.mark.parametrize("name", ["alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb"])
+def test_dense_full_size_sampled(mods, name):
+    gf, pl = mods
+    w = wl.config(name)
+    grads = wl.gradients(w, 0, device="cuda")
+    pipe = pl.Pipeline(w.sizes, w.P, 0, w.theta, w.loss_scale)
+    pipe.set_gradients(grads)
+    pipe.out_pool.fill_(-9.0)
+    pipe.step()
+    torch.cuda.synchronize()
+
+    lo, hi = ob.buckets(w.sizes, w.theta)
+    assert pipe.plan.n_buckets == len(lo)
+    rng = np.random.default_rng(7)
+    idx = [np.arange(0, 4096), np.arange(w.N - 4096, w.N)]
+    for a, b in zip(lo, hi):                          # both ends of every bucket and of its segments
+        seg = ob.ring_segment(b - a, w.P)
+        idx += [np.arange(a, min(b, a + 64)), np.arange(max(a, b - 64), b)]
+        for s in range(1, w.P):
+            e = a + s * seg
+            if e < b:
+                idx.append(np.arange(max(a, e - 16), min(b, e + 16)))
+    for _ in range(48):
+        st = int(rng.integers(0, w.N - 2048))
+        idx.append(np.arange(st, st + 2048))
+    idx = np.unique(np.concatenate(idx))
+    tidx = torch.from_numpy(idx).cuda()
+
+    g = np.stack([pool_of(grads[p])[tidx].cpu().numpy() for p in range(w.P)])        # [P, n] fp32
+    send = ob.cast_dense(g, w.loss_scale)
+    for p in range(w.P):
+        got = pipe.send[p][tidx].cpu().numpy()
+        assert np.array_equal(u16(got), send[p]), f"send[{p}]"
+    b_of = np.searchsorted(hi, idx, side="right")
+    seg_index = np.empty(idx.size, dtype=np.int64)
+    for b in np.unique(b_of):
+        m = b_of == b
+        seg_index[m] = (idx[m] - lo[b]) // ob.ring_segment(hi[b] - lo[b], w.P)
+    reduced = fold_in_ring_order(send, seg_index)
+    assert np.array_equal(u16(pipe.reduced[tidx].cpu().numpy()), reduced), "reduced"
+    out = ob.unpack_dense(reduced, np.float32(1.0) / np.float32(w.loss_scale))
+    assert np.array_equal(u32(pipe.out_pool[tidx].cpu().numpy()), u32(out)), "out"
+    assert torch.all(pipe.out_pool != -9.0)           # every element was written
+
+
+# --------------------------------------------------------------------- CSC
+
+@pytest.mark.parametrize("name", ["alexnet_csc", "resnet50_csc"])
+def test_csc_full_size_sampled(mods, name):
+    gf, pl = mods
+    w = wl.config(name)
+    P, N, C = w.P, w.N, w.chunk
+    nc = ob.n_chunks(N, C)
+    k = w.k_for(nc)
+    sig = wl.sigma_table(w)
+    gsets = [wl.gradients(w, t, device="cuda", sig=sig) for t in range(2)]
+    pipe = pl.Pipeline(w.sizes, P, C, w.theta, w.loss_scale, k=k, mu=w.mu, schedule="lagged")
+    assert pipe.n_chunks == nc
+    sync = torch.cuda.synchronize
+    alpha = np.float32(1.0) / np.float32(w.loss_scale)
+    rng = np.random.default_rng(11)
+    none = np.array([], dtype=np.int32)
+    first = np.array([0], dtype=np.int32)
+
+    def span(c):
+        return c * C, min(N, (c + 1) * C)
+
+    def g_chunks(t, chunks):
+        """{c: [P, len] fp32} cut from the GPU-resident gradients of iteration t (copied bits)."""
+        rows = {c: [] for c in chunks}
+        for p in range(P):
+            pool = pool_of(gsets[t][p])
+            for c in chunks:
+                a, b = span(c)
+                rows[c].append(pool[a:b].cpu().numpy())
+            del pool
+        return {c: np.stack(v) for c, v in rows.items()}
+
+    def dev_chunk(bufs, c):
+        a, b = span(c)
+        return np.stack([bufs[p][a:b].cpu().numpy() for p in range(P)])
+
+    def is_in(sel, c):
+        j = int(np.searchsorted(sel, c))
+        return (j < len(sel) and sel[j] == c), j
+
+    def check_norms(t, l1, acc, chunks):
+        for c in chunks:
+            want = ob.chunk_l1(np.ascontiguousarray(acc[c]), C)[:, 0]
+            assert np.allclose(l1[:, c], want, rtol=RTOL, atol=0), f"t={t} norm of chunk {c}"
+
+    def check_pack(t, sel, acc, chunks):
+        """send and historical gradient of the sampled chunks; returns {c: (hg, reduced or None, slot)}."""
+        L = ob.packed_len(N, C, sel)
+        assert int(pipe.packed_len.item()) == L
+        seg = ob.ring_segment(L, P)
+        state = {}
+        for c in chunks:
+            sent, j = is_in(sel, c)
+            acc_c = np.ascontiguousarray(acc[c])
+            n = acc_c.shape[1]
+            send_c, hg_c = ob.pack_residual(acc_c, n, first if sent else none, w.loss_scale, w.mu)
+            red = None
+            if sent:
+                got = np.stack([pipe.send[p][j * C:j * C + n].cpu().numpy() for p in range(P)])
+                assert np.array_equal(u16(got), send_c), f"t={t} send of chunk {c}"
+                red = fold_in_ring_order(send_c, (j * C + np.arange(n)) // seg)
+            assert np.array_equal(u32(dev_chunk(pipe.residual, c)), u32(hg_c)), f"t={t} hg of chunk {c}"
+            state[c] = (hg_c, red, j)
+        return state
+
+    def check_unpack(t, state, red_l1, chunks):
+        for c in chunks:
+            _, red, j = state[c]
+            a, b = span(c)
+            got = pipe.out_pool[a:b].cpu().numpy()
+            if red is None:
+                assert np.all(got == -9.0), f"t={t} chunk {c} was not sent but was written"
+                continue
+            assert np.array_equal(u16(pipe.reduced[j * C:j * C + (b - a)].cpu().numpy()), red), f"t={t} reduced {c}"
+            out = np.zeros(b - a, dtype=np.float32)
+            want_l1 = ob.unpack(red, b - a, b - a, first, alpha, out)
+            assert np.array_equal(u32(got), u32(out)), f"t={t} out of chunk {c}"
+            assert np.allclose(red_l1[j], want_l1[0], rtol=RTOL, atol=0), f"t={t} reduced norm of chunk {c}"
+
+    def check_selection(l1, sel_sent, red_l1):
+        sc = ob.score(l1) if sel_sent is None else ob.score(l1, sel_sent, red_l1)
+        assert np.array_equal(u32(pipe.scores.cpu().numpy()), u32(sc)), "scores are the checker's function of the norms"
+        sel = pipe.sel.cpu().numpy().copy()
+        assert np.array_equal(sel, ob.select(sc, k)[0]), "selection is the checker's top-k of the scores"
+        assert np.array_equal(np.flatnonzero(pipe.mask.cpu().numpy()), sel)
+        return sel
+
+    # ---------------- iteration 0: accumulate pass, selection, pack pass
+    pipe.set_gradients(gsets[0])
+    pipe.accum(); sync()
+    l1_0 = pipe.l1.cpu().numpy().reshape(P, nc).copy()
+    pipe.select(False); sync()
+    sel0 = check_selection(l1_0, None, None)
+    picked = [int(c) for c in rng.choice(sel0, size=4, replace=False)] + [int(sel0[0]), int(sel0[-1])]
+    others = [int(c) for c in rng.choice(nc, size=8, replace=False) if not is_in(sel0, c)[0]]
+    sample = sorted(set(picked + others + [0, nc - 1]))
+    zero = np.float32(0)
+    acc0 = {c: (g + zero).astype(np.float32) for c, g in g_chunks(0, sample).items()}   # zero initial hg
+    for c in sample:
+        assert np.array_equal(u32(dev_chunk(pipe.residual, c)), u32(acc0[c])), f"acc of chunk {c}"
+    check_norms(0, l1_0, acc0, sample)
+    pipe.pack(); sync()
+    st0 = check_pack(0, sel0, acc0, sample)
+    pipe.out_pool.fill_(-9.0)
+    pipe.ring(); pipe.unpack(); sync()
+    red_l1_0 = pipe.red_l1.cpu().numpy().copy()
+    check_unpack(0, st0, red_l1_0, sample)
+    pipe.select(True); sync()
+    sel1 = check_selection(l1_0, sel0, red_l1_0)
+
+    # ---------------- iteration 1: the single fused pass with the selection made above
+    extra = [int(c) for c in rng.choice(sel1, size=3, replace=False) if int(c) not in sample]
+    for c, g in g_chunks(0, extra).items():            # replay their first iteration in the checker
+        acc0[c] = (g + zero).astype(np.float32)
+        _, hg_c = ob.pack_residual(np.ascontiguousarray(acc0[c]), acc0[c].shape[1],
+                                   first if is_in(sel0, c)[0] else none, w.loss_scale, w.mu)
+        st0[c] = (hg_c, None, -1)
+    sample = sorted(set(sample + extra))
+    g1 = g_chunks(1, sample)
+    acc1 = {c: ob.accumulate(np.ascontiguousarray(g1[c]), np.ascontiguousarray(st0[c][0])) for c in sample}
+    pipe.set_gradients(gsets[1])
+    pipe.fused(); sync()
+    l1_1 = pipe.l1.cpu().numpy().reshape(P, nc).copy()
+    check_norms(1, l1_1, acc1, sample)
+    st1 = check_pack(1, sel1, acc1, sample)
+    pipe.out_pool.fill_(-9.0)
+    pipe.ring(); pipe.unpack(); sync()
+    red_l1_1 = pipe.red_l1.cpu().numpy().copy()
+    check_unpack(1, st1, red_l1_1, sample)
+    pipe.select(True); sync()
+    check_selection(l1_1, sel1, red_l1_1)
