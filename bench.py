@@ -29,7 +29,11 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
 # profiles/.  Keyed by workload; absent -> null in the JSON.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # k_fuse<MODE_FUSED>: FETCH 3 883 238.7 x 2.0000 KiB + WRITE 4 002 751.8 x 1.0000 KiB per launch
+    # (profiles/k_fuse_fused_alexnet_csc.md); counted between L2 and the fabric
+    "alexnet_csc": 7_952_796_700 + 4_098_817_843,
+}
 
 
 def algorithmic_bytes(w, k_elems_L: int, schedule: str):
