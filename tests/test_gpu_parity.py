@@ -274,10 +274,11 @@ def test_select_bit_exact_including_ties(gfm, nc, k):
     assert np.array_equal(sel.cpu().numpy(), np.arange(k))
 
 
-def test_select_after_allreduce_scores_sent_chunks_by_their_reduced_norm(gfm):
+@pytest.mark.parametrize("P,nc,k", [(6, 500, 50), (64, 20_000, 333)])   # the second takes the multi-kernel route
+def test_select_after_allreduce_scores_sent_chunks_by_their_reduced_norm(gfm, P, nc, k):
     gf, _ = gfm
     rng = np.random.default_rng(8)
-    P, nc, k, C = 6, 500, 50, 16
+    C = 16
     plan = gf.Plan([nc * C], 1 << 40, C, P)
     l1 = rng.random((P, nc)).astype(np.float32)
     prev = np.sort(rng.choice(nc, size=k, replace=False)).astype(np.int32)
