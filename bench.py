@@ -53,7 +53,8 @@ def algorithmic_bytes(w, k_elems_L: int, schedule: str):
     return sum(st.values()), st
 
 
-def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int, chunk=None):
+def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int, chunk=None,
+            all_stages: bool = False):
     import torch
     from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
 
@@ -95,7 +96,10 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     for _ in range(warmup):
         pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
     torch.cuda.synchronize()
-    pipe.probe = []
+    _, st_bytes = algorithmic_bytes(w, pipe.cap, schedule)
+    # events bracket only the dominant kernel unless a per-stage breakdown is asked for: every
+    # event is a packet between two kernels and costs a few microseconds of the step
+    pipe.probe, pipe.probe_only = [], (None if all_stages else max(st_bytes, key=st_bytes.get))
     t0 = time.perf_counter()
     for _ in range(steps):
         pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
@@ -185,6 +189,7 @@ def main() -> int:
     ap.add_argument("--others", default="alexnet_dense,resnet50_dense_4mb,resnet50_dense_64mb,resnet50_csc",
                     help="comma-separated extra workloads reported under config.others ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage-times", action="store_true", help="bracket every stage with events (adds a few us per step)")
     ap.add_argument("--chunk", type=int, default=None, help="override the workload's chunk size (tuning aid)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: first a plain elementwise copy of known size (2 GiB read, "
@@ -215,12 +220,12 @@ def main() -> int:
         torch.cuda.empty_cache()
         a.others, a.no_cpu_baseline = "", True
         steps, warmup, n_sets = 3, 2, 2
-    main_res = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk)
+    main_res = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk, a.stage_times)
     others = {}
     for nm in [x for x in a.others.split(",") if x and x != a.workload]:
         wo = wl.config(nm)
         so = max(10, wo.iterations)
-        r = run_gpu(nm, so, 5, a.input, a.schedule, 4 if wo.chunk else 2)
+        r = run_gpu(nm, so, 5, a.input, a.schedule, 4 if wo.chunk else 2, None, a.stage_times)
         others[nm] = {kk: r[kk] for kk in ("P", "N", "schedule", "n_buckets", "ms_per_step", "gbs", "payload_gbs",
                                             "stage_ms", "dominant", "dominant_ms")}
         others[nm]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS

@@ -68,6 +68,7 @@ class Pipeline:
         self.grads_tab = self.pools_tab = None
         self._keep = None
         self.probe = None            # list to collect (stage, start event, end event) per launch
+        self.probe_only = None       # bracket only this stage (fewer event packets between kernels)
 
     # ------------------------------------------------------------- inputs
     def set_gradients(self, grads: List[List[torch.Tensor]]) -> None:
@@ -136,7 +137,7 @@ class Pipeline:
     # ---------------------------------------------------------- iteration
     def _run(self, name: str, fn, after: bool = False) -> None:
         """Run one stage; with a probe list attached, bracket it with events on the launch stream."""
-        if self.probe is None:
+        if self.probe is None or (self.probe_only is not None and name != self.probe_only):
             fn(after) if name == "select" else fn()
             return
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
