@@ -36,7 +36,7 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def algorithmic_bytes(w, k_elems_L: int, schedule: str):
+def algorithmic_bytes(w, k_elems_L: int, schedule: str, sgd: bool = False):
     """Bytes the method must move per iteration (every gradient read once, the
     historical gradient read and written once, each wire element written once
     and read once per worker, the reduced buffer written once and read once,
@@ -50,11 +50,13 @@ def algorithmic_bytes(w, k_elems_L: int, schedule: str):
     else:
         st = {"accum": P * N * 12, "pack": P * L * (4 + ws + 4), "ring": L * (P * ws + ws),
               "unpack": L * (ws + 4), "select": 0}
+    if sgd:                                   # Algorithm 1's update step: hu and w read and written
+        st["unpack"] += L * 16
     return sum(st.values()), st
 
 
 def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int, chunk=None,
-            all_stages: bool = False):
+            all_stages: bool = False, sgd=None):
     import torch
     from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
 
@@ -70,7 +72,7 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     off, _, _ = probe_plan.layout()
     probe_plan.close()
     pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=pipe_k, mu=w.mu, wire=w.wire,
-                       schedule=schedule)
+                       schedule=schedule, sgd=sgd)
     # gradient sets resident in HBM: scattered per-tensor allocations (fusion is folded into the
     # read) or one pool per worker (the zero-copy layout)
     tables, keep = [], []
@@ -96,7 +98,7 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     for _ in range(warmup):
         pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
     torch.cuda.synchronize()
-    _, st_bytes = algorithmic_bytes(w, pipe.cap, schedule)
+    _, st_bytes = algorithmic_bytes(w, pipe.cap, schedule, sgd is not None)
     # events bracket only the dominant kernel unless a per-stage breakdown is asked for: every
     # event is a packet between two kernels and costs a few microseconds of the step
     pipe.probe, pipe.probe_only = [], (None if all_stages else max(st_bytes, key=st_bytes.get))
@@ -109,7 +111,7 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
 
     ms_per_step = (t1 - t0) * 1e3 / steps
     L = int(pipe.packed_len.item()) if w.chunk else w.N
-    total_bytes, per_stage_bytes = algorithmic_bytes(w, L, schedule)
+    total_bytes, per_stage_bytes = algorithmic_bytes(w, L, schedule, sgd is not None)
     stage_ms = {}
     for nm, e0, e1 in probe:
         stage_ms.setdefault(nm, []).append(e0.elapsed_time(e1))
@@ -232,6 +234,12 @@ def main() -> int:
         dom_b = r["stage_bytes"][r["dominant"]]
         others[nm]["dominant_gbs"] = dom_b / r["dominant_ms"] / 1e6
 
+    if w.chunk and not a.pmc_probe and a.others:
+        # the same workload with Algorithm 1's SGD-update step fused into the unpack
+        r = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk, a.stage_times, (0.9, -0.01))
+        others[a.workload + "+sgd_update"] = {kk: r[kk] for kk in ("P", "N", "schedule", "ms_per_step", "gbs",
+                                                                      "bytes_per_step", "stage_ms")}
+        others[a.workload + "+sgd_update"]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
     dom = main_res["dominant"]
     dom_bytes = main_res["stage_bytes"][dom]
     achieved = dom_bytes / main_res["dominant_ms"] / 1e6

@@ -204,6 +204,28 @@ gf_status gf_unpack_apply(const gf_plan *plan, const void *reduced, int64_t L,
                           float *out_pool, void *const *out_tensors,
                           float *reduced_l1, void *workspace, gf_stream stream);
 
+/* ------------------------------------------------------- gf_unpack_sgd_update
+ * gf_unpack_apply plus the SGD-update step of Algorithm 1 (momentum SGD
+ * correction) in the same pass.  With g = fp32(reduced) * alpha, at every
+ * element of an important chunk
+ *     hu = momentum * hu + learning_rate * g      (historical update)
+ *     w  = w + hu                                 (the update u_t is hu_t)
+ * each product and sum rounded to fp32 on its own; elsewhere hu and w are not
+ * touched (hu_t = hu_{t-1}, no update).  The sign convention is the paper's:
+ * the caller passes a negative learning_rate for descent.
+ * w / hu come either as N-element fp32 pools in the plan's layout (w_pool,
+ * hu_pool) or as device tables [m] of per-tensor fp32 buffers (w_tensors,
+ * hu_tensors); exactly one of the two forms.  out_pool (optional) also
+ * receives g as gf_unpack_apply would write it.  Other arguments as in
+ * gf_unpack_apply. */
+gf_status gf_unpack_sgd_update(const gf_plan *plan, const void *reduced, int64_t L,
+                               const int32_t *sel_idx, int32_t k, float alpha,
+                               float momentum, float learning_rate,
+                               float *w_pool, float *hu_pool,
+                               void *const *w_tensors, void *const *hu_tensors,
+                               float *out_pool, float *reduced_l1,
+                               void *workspace, gf_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

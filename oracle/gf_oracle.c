@@ -437,6 +437,32 @@ void gfo_unpack(int wire, const void *reduced, int64_t N, int64_t C,
     }
 }
 
+/* ------------------------------ Algorithm 1, SGD update step (Sec. 3.2)
+ * For a gradient in an important chunk: u = hu = momentum * hu + learningrate * g
+ * and w = w + u.  Anywhere else hu keeps its value and w is not updated.
+ * g is the unpacked reduced gradient; out (optional) receives it. */
+void gfo_sgd_update(int wire, const void *reduced, int64_t N, int64_t C,
+                    const int32_t *sel, int32_t k, float alpha, float momentum, float lr,
+                    float *w, float *hu, float *out)
+{
+    int64_t slot = 0;
+    for (int32_t j = 0; j < k; ++j) {
+        int64_t lo = (int64_t)sel[j] * C, len = chunk_len(N, C, sel[j]);
+        for (int64_t i = 0; i < len; ++i) {
+            float g = wire == 0 ? gfo_f16_to_f32(((const uint16_t *)reduced)[slot + i])
+                                : ((const float *)reduced)[slot + i];
+            g = g * alpha;
+            if (out) out[lo + i] = g;
+            float keep = momentum * hu[lo + i];
+            float step = lr * g;
+            float u = keep + step;
+            hu[lo + i] = u;
+            w[lo + i] = w[lo + i] + u;
+        }
+        slot += len;
+    }
+}
+
 void gfo_unpack_dense(int wire, const void *reduced, int64_t n, float alpha, float *out)
 {
     for (int64_t i = 0; i < n; ++i) {

@@ -1,7 +1,11 @@
-// gf_unpack_apply: reduced wire values back to fp32 times alpha, written into
-// the gradient pool and/or scattered to the per-tensor buffers, only at the
-// chunks that were sent (Section 2.5 second conversion; Section 3.2), plus the
-// L1 norm of each written chunk for the next selection.
+// gf_unpack_apply / gf_unpack_sgd_update: reduced wire values back to fp32
+// times alpha, only at the chunks that were sent (Section 2.5 second
+// conversion; Section 3.2), written into the gradient pool and/or scattered to
+// per-tensor buffers, plus the L1 norm of each written chunk for the next
+// selection.  The update variant also applies the SGD-update half of
+// Algorithm 1 (momentum SGD correction) in the same pass: at important chunks
+// hu = momentum * hu + learning_rate * g and w = w + hu; everything else is
+// left untouched (hu_t = hu_{t-1}, no weight update).
 #include "gf_device.h"
 
 namespace {
@@ -11,57 +15,83 @@ struct UnpackArgs {
     const int32_t *sel_idx;        // NULL: tile index = block index
     float *out_pool;
     void *const *out_tensors;
+    float *w_pool, *hu_pool;       // update variant, pool form
+    void *const *w_tensors, *const *hu_tensors;   // update variant, per-tensor form
     float *reduced_l1;
     const int32_t *piece_start;
     const gf_piece *pieces;
     int64_t N;
     int32_t tile;
-    float alpha;
+    float alpha, momentum, lr;
 };
 
-template <typename W>
-__device__ __forceinline__ void run(const W *src_, float *dst_, int len, float alpha, double &l1)
+// One contiguous run.  dst may be null in the update variant (gradient not kept).
+template <typename W, bool UPD, int NT>
+__device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, float *w_, int len,
+                                    const UnpackArgs &a, double &l1)
 {
     const GF_GLOBAL W *__restrict__ src = gf_global(src_);
     GF_GLOBAL float *__restrict__ dst = gf_global(dst_);
+    GF_GLOBAL float *__restrict__ hu = gf_global(hu_);
+    GF_GLOBAL float *__restrict__ w = gf_global(w_);
     using W4 = typename gf_wire4<W>::type;
-    const bool vec = gf_aligned(src, sizeof(W4)) && gf_aligned(dst, 16);
+    const float alpha = a.alpha, mom = a.momentum, lr = a.lr;
+    bool vec = gf_aligned(src, sizeof(W4)) && (!dst || gf_aligned(dst, 16));
+    if constexpr (UPD) vec = vec && gf_aligned(hu, 16) && gf_aligned(w, 16);
     const int nvec = vec ? (len >> 2) : 0;
     const GF_GLOBAL W4 *s4 = reinterpret_cast<const GF_GLOBAL W4 *>(src);
     GF_GLOBAL gf_f32x4 *d4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(dst);
+    GF_GLOBAL gf_f32x4 *h4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(hu);
+    GF_GLOBAL gf_f32x4 *w4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(w);
+
+    auto one = [&](int v, W4 x, gf_f32x4 hh, gf_f32x4 ww) {
+        float g0, g1, g2, g3;
+        gf_unpack4(x, g0, g1, g2, g3);
+        g0 *= alpha; g1 *= alpha; g2 *= alpha; g3 *= alpha;
+        l1 += static_cast<double>(fabsf(g0)); l1 += static_cast<double>(fabsf(g1));
+        l1 += static_cast<double>(fabsf(g2)); l1 += static_cast<double>(fabsf(g3));
+        if (dst) gf_st_stream(gf_pack4(g0, g1, g2, g3), &d4[v]);
+        if constexpr (UPD) {
+            // every product and sum rounds on its own (no contraction)
+            const gf_f32x4 hn = gf_pack4(mom * hh.x + lr * g0, mom * hh.y + lr * g1,
+                                         mom * hh.z + lr * g2, mom * hh.w + lr * g3);
+            gf_st_stream(hn, &h4[v]);
+            gf_st_stream(gf_pack4(ww.x + hn.x, ww.y + hn.y, ww.z + hn.z, ww.w + hn.w), &w4[v]);
+        }
+    };
+
     constexpr int U = 4;
     int v = threadIdx.x;
-    for (; v + (U - 1) * GF_BLOCK < nvec; v += U * GF_BLOCK) {
+    for (; v + (U - 1) * NT < nvec; v += U * NT) {
         W4 x[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = s4[v + u * GF_BLOCK];
+        gf_f32x4 hh[U] = {}, ww[U] = {};
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float a, b, c, d;
-            gf_unpack4(x[u], a, b, c, d);
-            a *= alpha; b *= alpha; c *= alpha; d *= alpha;
-            l1 += static_cast<double>(fabsf(a)); l1 += static_cast<double>(fabsf(b));
-            l1 += static_cast<double>(fabsf(c)); l1 += static_cast<double>(fabsf(d));
-            d4[v + u * GF_BLOCK] = gf_pack4(a, b, c, d);
+            x[u] = s4[v + u * NT];
+            if constexpr (UPD) { hh[u] = gf_ld_stream(&h4[v + u * NT]); ww[u] = gf_ld_stream(&w4[v + u * NT]); }
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) one(v + u * NT, x[u], hh[u], ww[u]);
     }
-    for (; v < nvec; v += GF_BLOCK) {
-        float a, b, c, d;
-        gf_unpack4(s4[v], a, b, c, d);
-        a *= alpha; b *= alpha; c *= alpha; d *= alpha;
-        l1 += static_cast<double>(fabsf(a)); l1 += static_cast<double>(fabsf(b));
-        l1 += static_cast<double>(fabsf(c)); l1 += static_cast<double>(fabsf(d));
-        d4[v] = gf_pack4(a, b, c, d);
+    for (; v < nvec; v += NT) {
+        gf_f32x4 hh = {}, ww = {};
+        if constexpr (UPD) { hh = gf_ld_stream(&h4[v]); ww = gf_ld_stream(&w4[v]); }
+        one(v, s4[v], hh, ww);
     }
-    for (int i = (nvec << 2) + threadIdx.x; i < len; i += GF_BLOCK) {
-        const float a = gf_from_wire<W>(src[i]) * alpha;
-        l1 += static_cast<double>(fabsf(a));
-        dst[i] = a;
+    for (int i = (nvec << 2) + threadIdx.x; i < len; i += NT) {
+        const float g = gf_from_wire<W>(src[i]) * alpha;
+        l1 += static_cast<double>(fabsf(g));
+        if (dst) dst[i] = g;
+        if constexpr (UPD) {
+            const float hn = mom * hu[i] + lr * g;
+            hu[i] = hn;
+            w[i] = w[i] + hn;
+        }
     }
 }
 
-template <typename W>
-__global__ __launch_bounds__(GF_BLOCK) void k_unpack(const UnpackArgs a)
+template <typename W, bool UPD, int NT>
+__global__ __launch_bounds__(NT) void k_unpack(const UnpackArgs a)
 {
     const int j = blockIdx.x;
     const int tile = a.sel_idx ? a.sel_idx[j] : j;
@@ -70,18 +100,70 @@ __global__ __launch_bounds__(GF_BLOCK) void k_unpack(const UnpackArgs a)
     const int tile_len = left < a.tile ? static_cast<int>(left) : a.tile;
     const W *src = static_cast<const W *>(a.reduced) + static_cast<int64_t>(j) * a.tile;
     double l1 = 0.0, unused = 0.0;
-    if (a.out_pool) run<W>(src, a.out_pool + tile_lo, tile_len, a.alpha, l1);
-    if (a.out_tensors) {
-        double &acc = a.out_pool ? unused : l1;     // count each element once
+    const bool pooled = a.out_pool || (UPD && a.w_pool);
+    if (pooled) {
+        float *out = a.out_pool ? a.out_pool + tile_lo : nullptr;
+        if (UPD && a.w_pool) run<W, UPD, NT>(src, out, a.hu_pool + tile_lo, a.w_pool + tile_lo, tile_len, a, l1);
+        else run<W, false, NT>(src, out, nullptr, nullptr, tile_len, a, l1);
+    }
+    if (a.out_tensors || (UPD && a.w_tensors)) {
+        // per-tensor destinations: walk the pieces of this tile
+        double &acc = pooled ? unused : l1;         // count each element once
         const int pe = a.piece_start[tile + 1];
         for (int i = a.piece_start[tile]; i < pe; ++i) {
             const gf_piece pc = a.pieces[i];
-            float *dst = static_cast<float *>(a.out_tensors[pc.tensor]) + pc.src_off;
-            run<W>(src + pc.dst_rel, dst, pc.len, a.alpha, acc);
+            float *dst = a.out_tensors ? static_cast<float *>(a.out_tensors[pc.tensor]) + pc.src_off : nullptr;
+            if constexpr (UPD) {
+                if (a.w_tensors) {
+                    run<W, true, NT>(src + pc.dst_rel, dst, static_cast<float *>(a.hu_tensors[pc.tensor]) + pc.src_off,
+                                 static_cast<float *>(a.w_tensors[pc.tensor]) + pc.src_off, pc.len, a, acc);
+                    continue;
+                }
+            }
+            if (dst) run<W, false, NT>(src + pc.dst_rel, dst, nullptr, nullptr, pc.len, a, acc);
         }
     }
-    const double s = gf_block_sum<GF_BLOCK>(l1);
+    const double s = gf_block_sum<NT>(l1);
     if (a.reduced_l1 && threadIdx.x == 0) a.reduced_l1[j] = static_cast<float>(s);
+}
+
+template <int NT>
+gf_status launch_unpack(const gf_plan *pl, const UnpackArgs &a, int32_t blocks, bool update, hipStream_t st)
+{
+    const bool h = pl->wire == GF_WIRE_F16;
+    if (update) {
+        if (h) hipLaunchKernelGGL((k_unpack<uint16_t, true, NT>), dim3(blocks), dim3(NT), 0, st, a);
+        else hipLaunchKernelGGL((k_unpack<float, true, NT>), dim3(blocks), dim3(NT), 0, st, a);
+    } else {
+        if (h) hipLaunchKernelGGL((k_unpack<uint16_t, false, NT>), dim3(blocks), dim3(NT), 0, st, a);
+        else hipLaunchKernelGGL((k_unpack<float, false, NT>), dim3(blocks), dim3(NT), 0, st, a);
+    }
+    GF_LAUNCH_CHECK();
+    return GF_OK;
+}
+
+gf_status unpack_common(const gf_plan *pl, UnpackArgs &a, int64_t L, int32_t k, bool update, gf_stream stream)
+{
+    int32_t blocks;
+    if (a.sel_idx) {
+        if (pl->chunk == 0 || k < 1 || k > pl->n_chunks) return GF_EINVAL;
+        const int64_t C = pl->chunk;
+        if (L <= (k - 1) * C || L > k * C) return GF_EINVAL;
+        blocks = k;
+    } else {
+        if (L != pl->N || a.reduced_l1) return GF_EINVAL;
+        blocks = pl->n_tiles;
+    }
+    if (!pl->on_device) return GF_ESTATE;
+    a.piece_start = pl->d_piece_start;
+    a.pieces = pl->d_pieces;
+    a.N = pl->N;
+    a.tile = pl->tile;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // few, long tiles (the selected chunks of a CSC plan) get 1024 threads each so that a
+    // couple of hundred workgroups still fill the chip
+    if (pl->tile >= 16384) return launch_unpack<1024>(pl, a, blocks, update, st);
+    return launch_unpack<GF_BLOCK>(pl, a, blocks, update, st);
 }
 
 }  // namespace
@@ -93,34 +175,36 @@ extern "C" gf_status gf_unpack_apply(const gf_plan *pl, const void *reduced, int
 {
     (void)workspace;
     if (!pl || !reduced || (!out_pool && !out_tensors)) return GF_EINVAL;
-    int32_t blocks;
-    if (sel_idx) {
-        if (pl->chunk == 0 || k < 1 || k > pl->n_chunks) return GF_EINVAL;
-        const int64_t C = pl->chunk;
-        if (L <= (k - 1) * C || L > k * C) return GF_EINVAL;
-        blocks = k;
-    } else {
-        if (L != pl->N || reduced_l1) return GF_EINVAL;
-        blocks = pl->n_tiles;
-    }
-    if (!pl->on_device) return GF_ESTATE;
-
     UnpackArgs a{};
     a.reduced = reduced;
     a.sel_idx = sel_idx;
     a.out_pool = out_pool;
     a.out_tensors = out_tensors;
     a.reduced_l1 = reduced_l1;
-    a.piece_start = pl->d_piece_start;
-    a.pieces = pl->d_pieces;
-    a.N = pl->N;
-    a.tile = pl->tile;
     a.alpha = alpha;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (pl->wire == GF_WIRE_F16)
-        hipLaunchKernelGGL((k_unpack<uint16_t>), dim3(blocks), dim3(GF_BLOCK), 0, st, a);
-    else
-        hipLaunchKernelGGL((k_unpack<float>), dim3(blocks), dim3(GF_BLOCK), 0, st, a);
-    GF_LAUNCH_CHECK();
-    return GF_OK;
+    return unpack_common(pl, a, L, k, false, stream);
+}
+
+extern "C" gf_status gf_unpack_sgd_update(const gf_plan *pl, const void *reduced, int64_t L,
+                                          const int32_t *sel_idx, int32_t k, float alpha,
+                                          float momentum, float learning_rate,
+                                          float *w_pool, float *hu_pool,
+                                          void *const *w_tensors, void *const *hu_tensors,
+                                          float *out_pool, float *reduced_l1,
+                                          void *workspace, gf_stream stream)
+{
+    (void)workspace;
+    if (!pl || !reduced) return GF_EINVAL;
+    const bool pool_form = w_pool && hu_pool && !w_tensors && !hu_tensors;
+    const bool tensor_form = w_tensors && hu_tensors && !w_pool && !hu_pool;
+    if (pool_form == tensor_form) return GF_EINVAL;
+    UnpackArgs a{};
+    a.reduced = reduced;
+    a.sel_idx = sel_idx;
+    a.out_pool = out_pool;
+    a.w_pool = w_pool; a.hu_pool = hu_pool;
+    a.w_tensors = w_tensors; a.hu_tensors = hu_tensors;
+    a.reduced_l1 = reduced_l1;
+    a.alpha = alpha; a.momentum = momentum; a.lr = learning_rate;
+    return unpack_common(pl, a, L, k, true, stream);
 }

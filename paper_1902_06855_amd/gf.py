@@ -35,7 +35,7 @@ EXPORTS = (
     "gf_status_string", "gf_plan_create", "gf_plan_to_device", "gf_plan_destroy", "gf_plan_info",
     "gf_plan_layout", "gf_plan_ring_segment", "gf_plan_tiles", "gf_plan_tile_pieces",
     "gf_plan_workspace_bytes", "gf_fuse_pack", "gf_chunk_score_select", "gf_ring_reduce_sim",
-    "gf_unpack_apply",
+    "gf_unpack_apply", "gf_unpack_sgd_update",
 )
 
 _vp, _i32, _i64, _u32, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_float
@@ -64,6 +64,8 @@ _chunk_score_select = _sig("gf_chunk_score_select", C.c_int, _vp, _vp, _vp, _vp,
                            _vp, _vp, _vp)
 _ring_reduce_sim = _sig("gf_ring_reduce_sim", C.c_int, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp)
 _unpack_apply = _sig("gf_unpack_apply", C.c_int, _vp, _vp, _i64, _vp, _i32, _f32, _vp, _vp, _vp, _vp, _vp)
+_unpack_sgd_update = _sig("gf_unpack_sgd_update", C.c_int, _vp, _vp, _i64, _vp, _i32, _f32, _f32, _f32, _vp, _vp, _vp,
+                          _vp, _vp, _vp, _vp, _vp)
 
 
 class GfError(RuntimeError):
@@ -197,3 +199,12 @@ def gf_unpack_apply(plan: Plan, reduced, L: int, *, sel_idx=None, k: int = 0, al
     _check(_unpack_apply(plan.handle, _dptr(reduced), int(L), _dptr(sel_idx), int(k), float(alpha),
                          _dptr(out_pool), _dptr(out_tensors), _dptr(reduced_l1), _dptr(workspace),
                          _stream(stream)), "gf_unpack_apply")
+
+
+def gf_unpack_sgd_update(plan: Plan, reduced, L: int, *, sel_idx=None, k: int = 0, alpha: float = 1.0,
+                         momentum: float, learning_rate: float, w_pool=None, hu_pool=None, w_tensors=None,
+                         hu_tensors=None, out_pool=None, reduced_l1=None, workspace=None, stream=None) -> None:
+    _check(_unpack_sgd_update(plan.handle, _dptr(reduced), int(L), _dptr(sel_idx), int(k), float(alpha),
+                              float(momentum), float(learning_rate), _dptr(w_pool), _dptr(hu_pool),
+                              _dptr(w_tensors), _dptr(hu_tensors), _dptr(out_pool), _dptr(reduced_l1),
+                              _dptr(workspace), _stream(stream)), "gf_unpack_sgd_update")

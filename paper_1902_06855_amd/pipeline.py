@@ -26,7 +26,8 @@ from . import gf
 class Pipeline:
     def __init__(self, sizes: Sequence[int], P: int, chunk: int, theta: int, loss_scale: float,
                  k: int = 0, mu: float = 1.0, wire: str = "f16", schedule: str = "lagged",
-                 scatter_out: bool = False, allgather: bool = False, device: str = "cuda"):
+                 scatter_out: bool = False, allgather: bool = False, device: str = "cuda",
+                 sgd: Optional[tuple] = None):
         assert schedule in ("lagged", "immediate")
         self.sizes, self.P, self.chunk, self.mu = list(sizes), int(P), int(chunk), float(mu)
         self.S, self.schedule, self.device = float(loss_scale), schedule, device
@@ -65,6 +66,17 @@ class Pipeline:
         if allgather:
             self.ag = [new(self.cap, self.wdtype) for _ in range(self.P)]
             self.ag_tab = gf.ptr_table(self.ag, device)
+        # sgd = (momentum, learning_rate): unpack also applies Algorithm 1's update step to
+        # weight and historical-update pools (or per-tensor buffers when scatter_out is set)
+        self.sgd = sgd
+        self.w = self.hu = self.w_tab = self.hu_tab = None
+        if sgd is not None:
+            if scatter_out:
+                self.w = [new(s, torch.float32) for s in self.sizes]
+                self.hu = [new(s, torch.float32) for s in self.sizes]
+                self.w_tab, self.hu_tab = gf.ptr_table(self.w, device), gf.ptr_table(self.hu, device)
+            else:
+                self.w, self.hu = new(self.N, torch.float32), new(self.N, torch.float32)
         self.grads_tab = self.pools_tab = None
         self._keep = None
         self.probe = None            # list to collect (stage, start event, end event) per launch
@@ -126,6 +138,14 @@ class Pipeline:
                                   workspace=self.ws)
 
     def unpack(self) -> None:
+        if self.sgd is not None:
+            pooled = self.w_tab is None
+            gf.gf_unpack_sgd_update(self.plan, self.reduced, self.cap, sel_idx=self.sel if self.chunk else None,
+                                    k=self.k, alpha=self.alpha, momentum=self.sgd[0], learning_rate=self.sgd[1],
+                                    w_pool=self.w if pooled else None, hu_pool=self.hu if pooled else None,
+                                    w_tensors=self.w_tab, hu_tensors=self.hu_tab, out_pool=self.out_pool,
+                                    reduced_l1=self.red_l1 if self.chunk else None, workspace=self.ws)
+            return
         if self.chunk:
             gf.gf_unpack_apply(self.plan, self.reduced, self.cap, sel_idx=self.sel, k=self.k, alpha=self.alpha,
                                out_pool=self.out_pool, out_tensors=self.out_tab, reduced_l1=self.red_l1,

@@ -155,3 +155,13 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert status(gf.gf_unpack_apply, dense, fake, 8192, reduced_l1=fake, out_pool=fake) == E
     assert status(gf.gf_unpack_apply, dense, fake, 8000, out_pool=fake) == E
     assert status(gf.gf_unpack_apply, csc, fake, 2000, sel_idx=fake, k=2, out_pool=fake) == S
+    # unpack + SGD update: weights and history in exactly one form
+    upd = dict(momentum=0.9, learning_rate=0.1)
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, **upd) == E
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_pool=fake, **upd) == E
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake,
+                  w_tensors=fake, hu_tensors=fake, **upd) == E
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_pool=fake, hu_tensors=fake, **upd) == E
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1025, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake, **upd) == E
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake, **upd) == S
+    assert status(gf.gf_unpack_sgd_update, dense, fake, 8192, w_tensors=fake, hu_tensors=fake, **upd) == S

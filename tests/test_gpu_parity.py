@@ -439,3 +439,71 @@ def test_step_runs_the_same_sequence(gfm):
         assert torch.equal(a.out_pool, b.out_pool) and torch.equal(a.sel, b.sel)
         for p in range(w.P):
             assert torch.equal(a.residual[p], b.residual[p])
+
+
+# --------------------------------------------- SGD update fused into the unpack
+
+@pytest.mark.parametrize("scatter", [False, True])
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+def test_sgd_update_step_of_algorithm_1(gfm, scatter, wire):
+    """Important chunks: hu = momentum*hu + lr*g, w += hu; everything else untouched; over several
+    lagged iterations so that chunks go in and out of the important set."""
+    gf, pl = gfm
+    w_ = odd_workload(P=3, chunk=96, wire=wire) if scatter else wl.scaled(wl.config("tiny"), 4)
+    w_.wire = wire
+    nc = ob.n_chunks(w_.N, w_.chunk)
+    k = w_.k_for(nc)
+    mom, lr = 0.9, -0.125
+    pipe = pl.Pipeline(w_.sizes, w_.P, w_.chunk, w_.theta, w_.loss_scale, k=k, wire=wire, schedule="lagged",
+                       scatter_out=scatter, sgd=(mom, lr))
+    rng = np.random.default_rng(5)
+    w_ref = rng.standard_normal(w_.N).astype(np.float32)
+    hu_ref = np.zeros(w_.N, dtype=np.float32)
+    if scatter:
+        for j, v in enumerate(op.views(w_ref, w_.sizes)):
+            pipe.w[j].copy_(torch.from_numpy(np.ascontiguousarray(v)))
+    else:
+        pipe.w.copy_(torch.from_numpy(w_ref))
+    st = op.new_state(w_.P, w_.N)
+    alpha = np.float32(1.0) / np.float32(w_.loss_scale)
+    for t in range(4):
+        grads = cpu_grads(w_, t)
+        pools = pools_np(grads, w_.sizes)
+        pipe.set_gradients(to_dev(grads))
+        pipe.out_pool.fill_(-3.0)
+        pipe.step()
+        torch.cuda.synchronize()
+        out = np.full(w_.N, np.float32(-3.0))
+        r = op.csc_iteration(st, pools, w_.chunk, k, w_.loss_scale, w_.mu, "lagged", wire, out=out)
+        assert np.array_equal(pipe.sel.cpu().numpy(), r["sel_next"])
+        ob.sgd_update(r["reduced"], w_.N, w_.chunk, r["sel"], alpha, mom, lr, w_ref, hu_ref, None, wire)
+        same_bits(pipe.out_pool, out, f"t={t} out")
+        if scatter:
+            for j, (wv, hv) in enumerate(zip(op.views(w_ref, w_.sizes), op.views(hu_ref, w_.sizes))):
+                same_bits(pipe.w[j], np.ascontiguousarray(wv), f"t={t} w tensor {j}")
+                same_bits(pipe.hu[j], np.ascontiguousarray(hv), f"t={t} hu tensor {j}")
+        else:
+            same_bits(pipe.w, w_ref, f"t={t} w")
+            same_bits(pipe.hu, hu_ref, f"t={t} hu")
+    assert np.any(hu_ref != 0) and np.any(hu_ref == 0)
+
+
+def test_sgd_update_dense_plan(gfm):
+    gf, pl = gfm
+    w_ = odd_workload(P=3, chunk=0)
+    pipe = pl.Pipeline(w_.sizes, w_.P, 0, w_.theta, w_.loss_scale, sgd=(0.5, 0.25))
+    w_ref = np.linspace(-1, 1, w_.N).astype(np.float32)
+    hu_ref = np.zeros(w_.N, dtype=np.float32)
+    pipe.w.copy_(torch.from_numpy(w_ref))
+    for t in range(2):
+        grads = cpu_grads(w_, t)
+        d = op.dense_iteration(pools_np(grads, w_.sizes), w_.sizes, w_.theta, w_.loss_scale)
+        pipe.set_gradients(to_dev(grads))
+        pipe.step()
+        torch.cuda.synchronize()
+        g = d["out"]
+        hu_ref = (np.float32(0.5) * hu_ref).astype(np.float32) + (np.float32(0.25) * g).astype(np.float32)
+        w_ref = w_ref + hu_ref
+        same_bits(pipe.out_pool, g, "dense out")
+        same_bits(pipe.hu, hu_ref, "dense hu")
+        same_bits(pipe.w, w_ref, "dense w")
