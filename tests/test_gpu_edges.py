@@ -1,0 +1,105 @@
+"""Degenerate and extreme cases of the path on the GPU, against the CPU checker."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import binding as ob, pipeline as op
+from paper_1902_06855_amd import workloads as wl
+
+from test_gpu_parity import _run_csc, _run_dense, same_bits, gfm  # noqa: F401  (gfm is a fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def _wl(sizes, P, chunk, density, S=32.0, theta=1 << 40, wire="f16"):
+    return wl.Workload("edge", list(sizes), P=P, chunk=chunk, density=density, loss_scale=S, theta=theta, wire=wire)
+
+
+@pytest.mark.parametrize("schedule", ["immediate", "lagged"])
+def test_one_worker(gfm, schedule):
+    # P = 1: the ring is the identity and both scoring rules coincide
+    _run_csc(gfm, _wl([4096, 1000, 24], 1, 256, 0.2), schedule, "gather", T=3)
+
+
+@pytest.mark.parametrize("schedule", ["immediate", "lagged"])
+def test_a_single_important_chunk_and_a_single_chunk_pool(gfm, schedule):
+    _run_csc(gfm, _wl([3000, 5000], 3, 512, 0.0001), schedule, "gather", T=3, k=1)     # k = 1: argmax
+    _run_csc(gfm, _wl([300, 500], 3, 4096, 1.0), schedule, "pool", T=2)                # C > N: one short chunk
+
+
+def test_chunks_of_eight_elements(gfm):
+    w = _wl([1000, 24, 8], 2, 8, 0.1)
+    pipe = _run_csc(gfm, w, "lagged", "gather", T=2)
+    assert pipe.n_chunks == 129
+
+
+def test_one_element_tensors_and_chunks_that_span_hundreds_of_tensors(gfm):
+    # 300 tensors of 1..24 elements inside 4096-element chunks: more pieces per tile than the
+    # LDS piece table holds, unaligned everywhere
+    rng = np.random.default_rng(0)
+    sizes = [int(s) for s in rng.integers(1, 25, size=300)] + [5000]
+    _run_csc(gfm, _wl(sizes, 2, 4096, 0.5), "lagged", "gather", T=2, scatter=True)
+    _run_dense(gfm, _wl(sizes, 2, 0, 1.0, theta=64), "gather")
+    # a few dozen aligned pieces per tile: the LDS piece table path
+    sizes = [64] * 40 + [8, 8, 16, 4096]
+    _run_csc(gfm, _wl(sizes, 3, 2048, 0.5), "lagged", "gather", T=2, scatter=True)
+    _run_dense(gfm, _wl(sizes, 3, 0, 1.0, theta=500), "gather")
+
+
+def test_gradient_tensors_at_odd_addresses(gfm):
+    """Scattered tensors that are only 4-byte aligned (views one element into their storage)."""
+    gf, pl = gfm
+    w = _wl([4096, 8192, 512], 2, 1024, 0.25)
+    nc = ob.n_chunks(w.N, w.chunk)
+    k = w.k_for(nc)
+    grads = wl.gradients(w, 0)
+    dev = [[torch.cat([torch.zeros(1 + (j + p) % 3), g]).cuda()[1 + (j + p) % 3:] for j, g in enumerate(row)]
+           for p, row in enumerate(grads)]
+    assert any(t.data_ptr() % 16 for row in dev for t in row)
+    pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=k, schedule="immediate")
+    pipe.set_gradients(dev)
+    pipe.step()
+    torch.cuda.synchronize()
+    pools = np.stack([op.fuse([x.numpy() for x in row], w.sizes) for row in grads])
+    st = op.new_state(w.P, w.N)
+    r = op.csc_iteration(st, pools, w.chunk, k, w.loss_scale, 1.0, "immediate")
+    assert np.array_equal(pipe.sel.cpu().numpy(), r["sel"])
+    same_bits(pipe.out_pool, r["out"], "out")
+    for p in range(w.P):
+        same_bits(pipe.residual[p], st.hg[p], f"hg[{p}]")
+
+
+def test_pool_beyond_two_to_the_31_elements(gfm):
+    """64-bit offsets: one worker, a 2^31 + 12 345 element pool, dense path, sampled against the checker."""
+    gf, pl = gfm
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 << 30:
+        pytest.skip("needs about 36 GB of free device memory")
+    big = (1 << 31) + 12_345
+    sizes = [1000, big - 1000 - 4096, 4096]
+    w = _wl(sizes, 1, 0, 1.0, S=8.0, theta=1 << 30)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    grads = [[torch.randn(s, generator=g, device="cuda", dtype=torch.float32) for s in sizes]]
+    pipe = pl.Pipeline(w.sizes, 1, 0, w.theta, w.loss_scale)
+    assert pipe.N == big and pipe.plan.n_buckets == 2
+    pipe.set_gradients(grads)
+    pipe.step()
+    torch.cuda.synchronize()
+    off, N = ob.layout(sizes)
+    rng = np.random.default_rng(1)
+    idx = np.unique(np.concatenate([np.arange(0, 5000), np.arange(big - 5000, big),
+                                    np.arange((1 << 31) - 3000, (1 << 31) + 3000),
+                                    rng.integers(0, big, size=20000)]))
+    tens = np.searchsorted(-np.asarray(off), -idx, side="left")        # offsets descend with the ID index
+    gs = np.empty(idx.size, dtype=np.float32)
+    for j in range(len(sizes)):
+        m = tens == j
+        if m.any():
+            gs[m] = grads[0][j][torch.from_numpy(idx[m] - off[j]).cuda()].cpu().numpy()
+    send = ob.cast_dense(gs[None, :], w.loss_scale)[0]
+    tidx = torch.from_numpy(idx).cuda()
+    assert np.array_equal(pipe.send[0][tidx].cpu().numpy().view(np.uint16), send)
+    assert np.array_equal(pipe.reduced[tidx].cpu().numpy().view(np.uint16), send)      # P = 1: identity
+    out = ob.unpack_dense(send, np.float32(1) / np.float32(w.loss_scale))
+    assert np.array_equal(pipe.out_pool[tidx].cpu().numpy().view(np.uint32), out.view(np.uint32))
