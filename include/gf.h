@@ -106,6 +106,18 @@ int32_t gf_plan_tile_pieces(const gf_plan *plan, int32_t tile, int32_t cap,
  * 256-byte aligned; its contents carry nothing between calls). */
 size_t gf_plan_workspace_bytes(const gf_plan *plan);
 
+/* Warm-up dense training (Section 3.2): over the first `warmup_iterations`
+ * iterations the sparsity ratio ramps linearly from zero to its final value
+ * 1 - final_density.  Returns the number of important chunks for 0-based
+ * iteration `iteration` of a CSC plan, computed in double precision as
+ *     s = (1 - final_density) * min(iteration, warmup_iterations) / warmup_iterations
+ *     k = ceil((1 - s) * n_chunks - 1e-9), clamped to [1, n_chunks]
+ * (warmup_iterations = 0: the final value from the start).  Host only.
+ * Returns -1 on bad input (dense plan, final_density outside (0, 1],
+ * negative counts). */
+int32_t gf_plan_warmup_k(const gf_plan *plan, double final_density, int64_t iteration,
+                         int64_t warmup_iterations);
+
 /* --------------------------------------------------------------- gf_fuse_pack
  * Lazy-allreduce fusion (Section 3.1), the allreduce-preprocess step of
  * Algorithm 1, the local chunk norms of Section 3.2, and the cast / pack of

@@ -40,6 +40,7 @@ _layout = _sig("gfo_layout", _i64, _vp, _i32, _vp)
 _buckets = _sig("gfo_buckets", _i32, _vp, _i32, _i64, _vp, _vp)
 _n_chunks = _sig("gfo_n_chunks", _i64, _i64, _i64)
 _packed_len = _sig("gfo_packed_len", _i64, _i64, _i64, _vp, _i32)
+_warmup_k = _sig("gfo_warmup_k", _i64, _i64, C.c_double, _i64, _i64)
 _accumulate_w = _sig("gfo_accumulate_workers", None, _vp, _vp, _vp, _i32, _i64)
 _chunk_l1 = _sig("gfo_chunk_l1", None, _vp, _i64, _i64, _vp)
 _chunk_l1_w = _sig("gfo_chunk_l1_workers", None, _vp, _i32, _i64, _i64, _vp)
@@ -107,6 +108,10 @@ def n_chunks(N: int, Cc: int) -> int:
 def packed_len(N: int, Cc: int, sel: np.ndarray) -> int:
     sel = np.ascontiguousarray(sel, dtype=np.int32)
     return int(_packed_len(int(N), int(Cc), _ptr(sel), len(sel)))
+
+
+def warmup_k(nc: int, final_density: float, t: int, warmup: int) -> int:
+    return int(_warmup_k(int(nc), float(final_density), int(t), int(warmup)))
 
 
 def accumulate(g: np.ndarray, hg: np.ndarray) -> np.ndarray:

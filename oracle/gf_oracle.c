@@ -177,6 +177,21 @@ int64_t gfo_packed_len(int64_t N, int64_t C, const int32_t *sel, int32_t k)
     return L;
 }
 
+/* Warm-up dense training (Sec. 3.2): start dense (zero sparsity ratio) and ramp
+ * the sparsity ratio linearly to its final value over the warm-up iterations.
+ * Returns how many chunks are important at 0-based iteration t. */
+int64_t gfo_warmup_k(int64_t n_chunks, double final_density, int64_t t, int64_t warmup)
+{
+    double final_sparsity = 1.0 - final_density;
+    double sparsity = final_sparsity;
+    if (warmup > 0 && t < warmup) sparsity = final_sparsity * (double)t / (double)warmup;
+    double density = 1.0 - sparsity;
+    int64_t k = (int64_t)ceil(density * (double)n_chunks - 1e-9);
+    if (k < 1) k = 1;
+    if (k > n_chunks) k = n_chunks;
+    return k;
+}
+
 /* ------------------------- Algorithm 1, allreduce preprocess: g = g + hg */
 void gfo_accumulate(const float *g, const float *hg, float *acc, int64_t n)
 {

@@ -70,10 +70,14 @@ def new_state(P: int, N: int) -> CscState:
 
 def csc_iteration(state: CscState, pools: np.ndarray, C: int, k: int, S: float, mu: float,
                   schedule: str = "lagged", wire: str = "f16",
-                  out: Optional[np.ndarray] = None,
+                  out: Optional[np.ndarray] = None, k_next: Optional[int] = None,
                   choose: Optional[Callable[[str, np.ndarray, np.ndarray], np.ndarray]] = None
                   ) -> Dict[str, np.ndarray]:
     """One iteration; updates `state` in place and returns every intermediate.
+
+    k is the number of important chunks of this iteration; k_next (default k)
+    is how many the lagged schedule picks for the next one (warm-up changes it
+    from iteration to iteration).
 
     choose(stage, score, sel) may replace a selection (stage is "pre" for one
     taken before packing, "post" for one taken after the allreduce); tests use
@@ -106,7 +110,7 @@ def csc_iteration(state: CscState, pools: np.ndarray, C: int, k: int, S: float, 
 
     if schedule == "lagged":
         sc = ob.score(l1, sel, red_l1)
-        nxt, _ = ob.select(sc, k)
+        nxt, _ = ob.select(sc, k if k_next is None else k_next)
         if choose is not None:
             nxt = choose("post", sc, nxt)
         state.sel = nxt

@@ -2,6 +2,7 @@
 // table (Section 3.2), ring segments (Section 2.4), and the device copies of
 // the tables the kernels index.
 #include <algorithm>
+#include <cmath>
 #include <limits>
 #include <new>
 
@@ -219,4 +220,24 @@ extern "C" size_t gf_plan_workspace_bytes(const gf_plan *pl)
 {
     if (!pl) return 0;
     return gf_ws_total_bytes(pl);
+}
+
+// Warm-up dense training (Section 3.2): the sparsity ratio ramps linearly from
+// zero to its final value over the warm-up iterations.
+extern "C" int32_t gf_plan_warmup_k(const gf_plan *pl, double final_density, int64_t iteration,
+                                    int64_t warmup_iterations)
+{
+    if (!pl || pl->chunk == 0 || !(final_density > 0.0) || final_density > 1.0 || iteration < 0 ||
+        warmup_iterations < 0)
+        return -1;
+    double s = 1.0 - final_density;
+    if (warmup_iterations > 0) {
+        const int64_t t = iteration < warmup_iterations ? iteration : warmup_iterations;
+        s = s * static_cast<double>(t) / static_cast<double>(warmup_iterations);
+    }
+    const double want = std::ceil((1.0 - s) * static_cast<double>(pl->n_chunks) - 1e-9);
+    int64_t k = static_cast<int64_t>(want);
+    if (k < 1) k = 1;
+    if (k > pl->n_chunks) k = pl->n_chunks;
+    return static_cast<int32_t>(k);
 }

@@ -34,7 +34,7 @@ GF_PHASE_ACCUM, GF_PHASE_PACK = 1, 2
 EXPORTS = (
     "gf_status_string", "gf_plan_create", "gf_plan_to_device", "gf_plan_destroy", "gf_plan_info",
     "gf_plan_layout", "gf_plan_ring_segment", "gf_plan_tiles", "gf_plan_tile_pieces",
-    "gf_plan_workspace_bytes", "gf_fuse_pack", "gf_chunk_score_select", "gf_ring_reduce_sim",
+    "gf_plan_workspace_bytes", "gf_plan_warmup_k", "gf_fuse_pack", "gf_chunk_score_select", "gf_ring_reduce_sim",
     "gf_unpack_apply", "gf_unpack_sgd_update",
 )
 
@@ -59,6 +59,7 @@ _plan_tiles = _sig("gf_plan_tiles", _i32, _vp)
 _plan_tile_pieces = _sig("gf_plan_tile_pieces", _i32, _vp, _i32, _i32, C.POINTER(_i32), C.POINTER(_i64),
                          C.POINTER(_i32))
 _plan_workspace_bytes = _sig("gf_plan_workspace_bytes", C.c_size_t, _vp)
+_plan_warmup_k = _sig("gf_plan_warmup_k", _i32, _vp, C.c_double, _i64, _i64)
 _fuse_pack = _sig("gf_fuse_pack", C.c_int, _vp, _u32, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp, _vp)
 _chunk_score_select = _sig("gf_chunk_score_select", C.c_int, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
                            _vp, _vp, _vp)
@@ -149,6 +150,12 @@ class Plan:
         t, s, l = (_i32 * n)(), (_i64 * n)(), (_i32 * n)()
         _plan_tile_pieces(self.handle, int(tile), n, t, s, l)
         return [(t[i], s[i], l[i]) for i in range(n)]
+
+    def warmup_k(self, final_density: float, iteration: int, warmup_iterations: int) -> int:
+        k = int(_plan_warmup_k(self.handle, float(final_density), int(iteration), int(warmup_iterations)))
+        if k < 0:
+            raise GfError(GF_EINVAL, "gf_plan_warmup_k")
+        return k
 
     def workspace_bytes(self) -> int:
         return int(_plan_workspace_bytes(self.handle))

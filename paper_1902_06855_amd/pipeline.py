@@ -27,7 +27,7 @@ class Pipeline:
     def __init__(self, sizes: Sequence[int], P: int, chunk: int, theta: int, loss_scale: float,
                  k: int = 0, mu: float = 1.0, wire: str = "f16", schedule: str = "lagged",
                  scatter_out: bool = False, allgather: bool = False, device: str = "cuda",
-                 sgd: Optional[tuple] = None):
+                 sgd: Optional[tuple] = None, k_max: Optional[int] = None):
         assert schedule in ("lagged", "immediate")
         self.sizes, self.P, self.chunk, self.mu = list(sizes), int(P), int(chunk), float(mu)
         self.S, self.schedule, self.device = float(loss_scale), schedule, device
@@ -36,27 +36,30 @@ class Pipeline:
         self.wdtype = torch.float16 if wire == "f16" else torch.float32
         self.plan = gf.Plan(self.sizes, min(int(theta), 1 << 60), self.chunk, self.P, self.wire)
         self.N, self.n_chunks, self.m = self.plan.N, self.plan.n_chunks, len(self.sizes)
-        self.k = int(k) if self.chunk else 0
+        # k: important chunks in the current selection; k_next: how many the next selection
+        # takes (warm-up changes it between iterations); buffers are sized for k_max
+        self.k = self.k_next = int(k) if self.chunk else 0
+        self.k_max = max(int(k_max or 0), self.k)
         self.ws = self.plan.workspace()
         self.t = 0
         new = lambda n, dt: torch.zeros(n, dtype=dt, device=device)
         if self.chunk:
-            assert 1 <= self.k <= self.n_chunks
-            self.cap = self.k * self.chunk                      # packed-buffer capacity, elements
+            assert 1 <= self.k <= self.k_max <= self.n_chunks
+            self.cap_max = self.k_max * self.chunk              # packed-buffer capacity, elements
             self.residual = [new(self.N, torch.float32) for _ in range(self.P)]
             self.residual_tab = gf.ptr_table(self.residual, device)
             self.l1 = new(self.P * self.n_chunks, torch.float32)
             self.scores = new(self.n_chunks, torch.float32)
-            self.sel = new(self.k, torch.int32)
+            self.sel = new(self.k_max, torch.int32)
             self.mask = new(self.n_chunks, torch.uint8)
             self.packed_len = new(1, torch.int64)
-            self.red_l1 = new(self.k, torch.float32)
+            self.red_l1 = new(self.k_max, torch.float32)
         else:
-            self.cap = self.N
+            self.cap_max = self.N
             self.residual = None
-        self.send = [new(self.cap, self.wdtype) for _ in range(self.P)]
+        self.send = [new(self.cap_max, self.wdtype) for _ in range(self.P)]
         self.send_tab = gf.ptr_table(self.send, device)
-        self.reduced = new(self.cap, self.wdtype)
+        self.reduced = new(self.cap_max, self.wdtype)
         self.out_pool = new(self.N, torch.float32)
         self.out_tensors = self.out_tab = None
         if scatter_out:
@@ -64,7 +67,7 @@ class Pipeline:
             self.out_tab = gf.ptr_table(self.out_tensors, device)
         self.ag = self.ag_tab = None
         if allgather:
-            self.ag = [new(self.cap, self.wdtype) for _ in range(self.P)]
+            self.ag = [new(self.cap_max, self.wdtype) for _ in range(self.P)]
             self.ag_tab = gf.ptr_table(self.ag, device)
         # sgd = (momentum, learning_rate): unpack also applies Algorithm 1's update step to
         # weight and historical-update pools (or per-tensor buffers when scatter_out is set)
@@ -81,6 +84,11 @@ class Pipeline:
         self._keep = None
         self.probe = None            # list to collect (stage, start event, end event) per launch
         self.probe_only = None       # bracket only this stage (fewer event packets between kernels)
+
+    @property
+    def cap(self) -> int:
+        """Upper bound of the packed length for the current selection (elements)."""
+        return self.k * self.chunk if self.chunk else self.N
 
     # ------------------------------------------------------------- inputs
     def set_gradients(self, grads: List[List[torch.Tensor]]) -> None:
@@ -109,11 +117,12 @@ class Pipeline:
         """Choose self.sel (in place); after_allreduce scores the chunks just sent by their reduced norm."""
         if after_allreduce:
             gf.gf_chunk_score_select(self.plan, self.l1, reduced_l1=self.red_l1, prev_sel=self.sel, k_prev=self.k,
-                                     k=self.k, scores=self.scores, sel_idx=self.sel, mask=self.mask,
+                                     k=self.k_next, scores=self.scores, sel_idx=self.sel, mask=self.mask,
                                      packed_len=self.packed_len, workspace=self.ws)
         else:
-            gf.gf_chunk_score_select(self.plan, self.l1, k=self.k, scores=self.scores, sel_idx=self.sel,
+            gf.gf_chunk_score_select(self.plan, self.l1, k=self.k_next, scores=self.scores, sel_idx=self.sel,
                                      mask=self.mask, packed_len=self.packed_len, workspace=self.ws)
+        self.k = self.k_next
 
     def pack(self) -> None:
         gf.gf_fuse_pack(self.plan, gf.GF_PHASE_PACK, residual=self.residual_tab, sel_idx=self.sel, k=self.k,

@@ -57,6 +57,18 @@ def test_plan_matches_the_checker(name):
     plan.close()
 
 
+def test_warmup_schedule_matches_the_checker():
+    plan = gf.Plan([1000 * 64], 1 << 40, 64, 2, to_device=False)
+    for d, T in ((0.1, 10), (0.25, 4), (0.15, 7), (1.0, 5), (0.01, 0)):
+        for t in range(0, 14):
+            assert plan.warmup_k(d, t, T) == ob.warmup_k(plan.n_chunks, d, t, T)
+    dense = gf.Plan([100], 1 << 40, 0, 2, to_device=False)
+    for bad in (lambda: dense.warmup_k(0.1, 0, 1), lambda: plan.warmup_k(0.0, 0, 1), lambda: plan.warmup_k(1.5, 0, 1),
+                lambda: plan.warmup_k(0.1, -1, 1), lambda: plan.warmup_k(0.1, 0, -1)):
+        with pytest.raises(gf.GfError):
+            bad()
+
+
 def test_ring_segment_fp32_wire():
     plan = gf.Plan([100, 200], 1 << 40, 0, 6, wire=gf.GF_WIRE_F32, to_device=False)
     for L in (0, 1, 5, 24, 25, 300):

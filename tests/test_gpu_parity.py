@@ -507,3 +507,37 @@ def test_sgd_update_dense_plan(gfm):
         same_bits(pipe.out_pool, g, "dense out")
         same_bits(pipe.hu, hu_ref, "dense hu")
         same_bits(pipe.w, w_ref, "dense w")
+
+
+def test_warmup_changes_the_number_of_important_chunks_every_iteration(gfm):
+    """Lagged schedule with the dense-to-sparse warm-up ramp: k differs between consecutive iterations."""
+    gf, pl = gfm
+    w = wl.scaled(wl.config("tiny"), 4)
+    nc = ob.n_chunks(w.N, w.chunk)
+    T_w, final = 4, 0.25
+    pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=nc, k_max=nc, schedule="lagged")
+    ks = [pipe.plan.warmup_k(final, t, T_w) for t in range(8)]
+    assert ks[0] == nc and ks[-1] == w.k_for(nc) and len(set(ks)) >= 4
+    st = op.new_state(w.P, w.N)
+    for t in range(7):
+        grads = cpu_grads(w, t)
+        pipe.set_gradients(to_dev(grads))
+        pipe.k_next = ks[t] if t == 0 else ks[t + 1]     # iteration 0 selects twice: for itself, then for t = 1
+        pipe.out_pool.fill_(-2.0)
+        if t == 0:
+            pipe.accum(); pipe.select(False); pipe.pack(); pipe.ring(); pipe.unpack()
+            pipe.k_next = ks[1]
+            pipe.select(True)
+            pipe.t = 1
+        else:
+            pipe.step()
+        torch.cuda.synchronize()
+        out = np.full(w.N, np.float32(-2.0))
+        r = op.csc_iteration(st, pools_np(grads, w.sizes), w.chunk, ks[t], w.loss_scale, w.mu, "lagged",
+                             out=out, k_next=ks[t + 1])
+        assert pipe.k == ks[t + 1]
+        assert np.array_equal(pipe.sel[:pipe.k].cpu().numpy(), r["sel_next"]), f"t={t} next selection"
+        assert int(pipe.packed_len.item()) == ob.packed_len(w.N, w.chunk, r["sel_next"])
+        same_bits(pipe.out_pool, out, f"t={t} out")
+        for p in range(w.P):
+            same_bits(pipe.residual[p], st.hg[p], f"t={t} hg[{p}]")

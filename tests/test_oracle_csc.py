@@ -224,3 +224,31 @@ def test_unselected_positions_of_the_output_are_not_written():
     for j, c in enumerate(r["sel"]):
         seg = out[c * w.chunk:min(w.N, (c + 1) * w.chunk)].astype(np.float64)
         assert r["red_l1"][j] == pytest.approx(np.abs(seg).sum(), rel=1e-6)
+
+
+# ------------------------------------------------------------ warm-up schedule
+
+def test_warmup_starts_dense_and_ramps_the_sparsity_linearly():
+    # Section 3.2: zero sparsity at the start, linear ramp to the final sparsity, then constant
+    nc, d, T = 1000, 0.1, 10
+    ks = [ob.warmup_k(nc, d, t, T) for t in range(15)]
+    assert ks[0] == nc                                   # dense training at iteration 0
+    assert ks[10:] == [100] * 5                          # final density afterwards
+    assert all(a >= b for a, b in zip(ks, ks[1:]))       # never denser again
+    # sparsity(t) = 0.9 * t / 10  ->  k = 1000 * (1 - 0.09 t)
+    assert ks[:11] == [1000, 910, 820, 730, 640, 550, 460, 370, 280, 190, 100]
+    assert ob.warmup_k(nc, d, 0, 0) == 100               # no warm-up: final value at once
+    assert ob.warmup_k(7, 0.01, 99, 3) == 1              # at least one chunk
+    assert ob.warmup_k(245, 0.25, 10, 4) == 62 and ob.warmup_k(245, 0.25, 2, 4) == 154   # ceil(245 * 0.625)
+
+
+def test_lagged_iterations_follow_a_changing_chunk_count():
+    w = small(P=3, C=64, density=0.2)
+    nc = ob.n_chunks(w.N, w.chunk)
+    ks = [ob.warmup_k(nc, 0.2, t, 3) for t in range(6)]
+    st = op.new_state(w.P, w.N)
+    for t in range(5):
+        r = op.csc_iteration(st, _pools(w, t), w.chunk, ks[t], w.loss_scale, 1.0, "lagged", k_next=ks[t + 1])
+        assert len(r["sel"]) == ks[t] and len(r["sel_next"]) == ks[t + 1]
+        if t == 0:
+            assert np.all(st.hg == 0)                    # iteration 0 is dense: nothing held back
