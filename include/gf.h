@@ -189,9 +189,14 @@ gf_status gf_chunk_score_select(const gf_plan *plan, const float *chunk_l1,
  * r+1; the all-gather hops are copies.
  *
  * sendbuf: device table [P] of wire-typed buffers of L elements.
- * CSC plan: one ring over [0, L).  If L_dev is non-NULL it points to a device
- *   int64 holding the actual length (0 <= *L_dev <= L) and L only sizes the
- *   launch; this lets the length come straight from gf_chunk_score_select.
+ * CSC plan: the packed buffer [0, L) is reduced bucket by bucket, each bucket
+ *   a ring of its own (Section 3.2: CSC starts an allreduce once the buffer
+ *   holds more than theta): packed chunks are taken in order and a bucket
+ *   closes after the chunk that makes the waited size strictly greater than
+ *   theta_elems; the rest is flushed.  With theta_elems >= L that is one ring
+ *   over [0, L).  If L_dev is non-NULL it points to a device int64 holding the
+ *   actual length (0 <= *L_dev <= L) and L only sizes the launch; this lets
+ *   the length come straight from gf_chunk_score_select.
  * Dense plan: L must be N, L_dev NULL; every lazy-allreduce bucket is reduced
  *   as a ring of its own (its own segments), all in one launch.
  * reduced: device, L wire elements out.  allgather_out: NULL, or a device

@@ -40,6 +40,7 @@ _layout = _sig("gfo_layout", _i64, _vp, _i32, _vp)
 _buckets = _sig("gfo_buckets", _i32, _vp, _i32, _i64, _vp, _vp)
 _n_chunks = _sig("gfo_n_chunks", _i64, _i64, _i64)
 _packed_len = _sig("gfo_packed_len", _i64, _i64, _i64, _vp, _i32)
+_packed_buckets = _sig("gfo_packed_buckets", _i32, _i64, _i64, _vp, _i32, _i64, _vp, _vp)
 _warmup_k = _sig("gfo_warmup_k", _i64, _i64, C.c_double, _i64, _i64)
 _accumulate_w = _sig("gfo_accumulate_workers", None, _vp, _vp, _vp, _i32, _i64)
 _chunk_l1 = _sig("gfo_chunk_l1", None, _vp, _i64, _i64, _vp)
@@ -108,6 +109,14 @@ def n_chunks(N: int, Cc: int) -> int:
 def packed_len(N: int, Cc: int, sel: np.ndarray) -> int:
     sel = np.ascontiguousarray(sel, dtype=np.int32)
     return int(_packed_len(int(N), int(Cc), _ptr(sel), len(sel)))
+
+
+def packed_buckets(N: int, Cc: int, sel: np.ndarray, theta: int) -> Tuple[np.ndarray, np.ndarray]:
+    sel = np.ascontiguousarray(sel, dtype=np.int32)
+    lo = np.empty(len(sel), dtype=np.int64)
+    hi = np.empty(len(sel), dtype=np.int64)
+    nb = _packed_buckets(int(N), int(Cc), _ptr(sel), len(sel), int(theta), _ptr(lo), _ptr(hi))
+    return lo[:nb].copy(), hi[:nb].copy()
 
 
 def warmup_k(nc: int, final_density: float, t: int, warmup: int) -> int:

@@ -177,6 +177,28 @@ int64_t gfo_packed_len(int64_t N, int64_t C, const int32_t *sel, int32_t k)
     return L;
 }
 
+/* CSC relies on lazy allreduce as well (Sec. 3.2): important chunks are copied
+ * to the buffer as they fill, in generation order, and an allreduce starts on
+ * what is waiting once that is more than theta.  Returns the number of
+ * buckets of the packed buffer; bucket b covers packed range [lo[b], hi[b]). */
+int32_t gfo_packed_buckets(int64_t N, int64_t C, const int32_t *sel, int32_t k, int64_t theta,
+                           int64_t *lo, int64_t *hi)
+{
+    int32_t nb = 0;
+    int64_t start = 0, pos = 0, waited = 0;
+    for (int32_t j = 0; j < k; ++j) {
+        int64_t len = chunk_len(N, C, sel[j]);
+        pos += len;
+        waited += len;
+        if (waited > theta) {
+            lo[nb] = start; hi[nb] = pos; ++nb;
+            start = pos; waited = 0;
+        }
+    }
+    if (waited > 0) { lo[nb] = start; hi[nb] = pos; ++nb; }
+    return nb;
+}
+
 /* Warm-up dense training (Sec. 3.2): start dense (zero sparsity ratio) and ramp
  * the sparsity ratio linearly to its final value over the warm-up iterations.
  * Returns how many chunks are important at 0-based iteration t. */

@@ -71,13 +71,15 @@ def new_state(P: int, N: int) -> CscState:
 def csc_iteration(state: CscState, pools: np.ndarray, C: int, k: int, S: float, mu: float,
                   schedule: str = "lagged", wire: str = "f16",
                   out: Optional[np.ndarray] = None, k_next: Optional[int] = None,
+                  theta: int = 1 << 60,
                   choose: Optional[Callable[[str, np.ndarray, np.ndarray], np.ndarray]] = None
                   ) -> Dict[str, np.ndarray]:
     """One iteration; updates `state` in place and returns every intermediate.
 
     k is the number of important chunks of this iteration; k_next (default k)
     is how many the lagged schedule picks for the next one (warm-up changes it
-    from iteration to iteration).
+    from iteration to iteration).  theta is the lazy-allreduce threshold on the
+    packed buffer: each bucket of it is reduced by a ring allreduce of its own.
 
     choose(stage, score, sel) may replace a selection (stage is "pre" for one
     taken before packing, "post" for one taken after the allreduce); tests use
@@ -102,7 +104,11 @@ def csc_iteration(state: CscState, pools: np.ndarray, C: int, k: int, S: float, 
 
     send, hg = ob.pack_residual(acc, C, sel, S, mu, wire)
     state.hg = hg
-    reduced = ob.ring_fold(send, wire)
+    reduced = np.empty(send.shape[1], dtype=send.dtype)
+    b_lo, b_hi = ob.packed_buckets(N, C, sel, theta)
+    for a, b in zip(b_lo, b_hi):
+        reduced[a:b] = ob.ring_fold(np.ascontiguousarray(send[:, a:b]), wire)
+    r["packed_bucket_lo"], r["packed_bucket_hi"] = b_lo, b_hi
     if out is None:
         out = np.zeros(N, dtype=np.float32)
     red_l1 = ob.unpack(reduced, N, C, sel, np.float32(1.0) / np.float32(S), out, wire)

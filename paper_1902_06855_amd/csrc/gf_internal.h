@@ -74,6 +74,15 @@ inline int64_t gf_ring_segment_len(int64_t L, int32_t P, gf_wire w)
     return (per + A - 1) / A * A;
 }
 
+// Elements per full lazy-allreduce bucket of a CSC plan's packed buffer: the
+// bucket closes after the chunk that makes the waited size exceed theta.
+inline int64_t gf_csc_bucket_span(const gf_plan *p)
+{
+    int64_t q = p->theta / p->chunk + 1;
+    if (q > p->n_chunks) q = p->n_chunks;
+    return q * p->chunk;
+}
+
 // Threads per workgroup of the streaming kernels, and 16-byte groups each ring
 // workgroup covers.
 constexpr int GF_BLOCK = 256;

@@ -32,7 +32,8 @@ struct RingArgs {
     const int64_t *L_dev;
     int64_t L;
     int32_t P;
-    int32_t blocks_per_segment;       // single-ring launches
+    int32_t blocks_per_segment;       // CSC plans: workgroups per segment of a full bucket
+    int64_t bucket_span;              // CSC plans: elements per full bucket of the packed buffer
 };
 
 template <typename W> struct vec16;
@@ -65,13 +66,22 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
         lo = bk.lo; hi = bk.hi; seg = bk.seg;
         s = rb.segment; bis = rb.block_in_segment;
     } else {
+        // Packed buffer of a CSC plan.  All packed chunks have C elements (only the pool's
+        // last chunk can be short, and it is packed last), so the lazy-allreduce rule "flush
+        // when more than theta is waiting" closes a bucket every floor(theta / C) + 1 chunks:
+        // buckets are [b * span, min(L, (b + 1) * span)).
         int64_t L = a.L;
         if (a.L_dev) { const int64_t d = *a.L_dev; L = d < 0 ? 0 : (d < L ? d : L); }
-        lo = 0; hi = L;
-        const int64_t per = (L + P - 1) / P;
+        const int per_bucket = P * a.blocks_per_segment;
+        const int b = blockIdx.x / per_bucket;
+        const int r = blockIdx.x - b * per_bucket;
+        lo = static_cast<int64_t>(b) * a.bucket_span;
+        if (lo >= L) return;
+        hi = lo + a.bucket_span < L ? lo + a.bucket_span : L;
+        const int64_t per = (hi - lo + P - 1) / P;
         seg = (per + A - 1) / A * A;
-        s = blockIdx.x / a.blocks_per_segment;
-        bis = blockIdx.x - s * a.blocks_per_segment;
+        s = r / a.blocks_per_segment;
+        bis = r - s * a.blocks_per_segment;
     }
     const int64_t Lb = hi - lo;
     int64_t seg_lo = static_cast<int64_t>(s) * seg; if (seg_lo > Lb) seg_lo = Lb;
@@ -159,12 +169,16 @@ extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *se
     } else {
         if (L == 0) return GF_OK;
         const int64_t A = gf_wire_granule(pl->wire);
-        const int64_t seg = gf_ring_segment_len(L, pl->P, pl->wire);   // upper bound when L_dev is used
+        const int64_t span = gf_csc_bucket_span(pl);
+        const int64_t full = span < L ? span : L;                      // longest bucket (upper bound with L_dev)
+        const int64_t n_buckets = (L + span - 1) / span;
+        const int64_t seg = gf_ring_segment_len(full, pl->P, pl->wire);
         const int64_t groups = seg / A;
         const int64_t bps = (groups + GF_RING_GROUPS_PER_BLOCK - 1) / GF_RING_GROUPS_PER_BLOCK;
-        if (bps * pl->P > (int64_t{1} << 30)) return GF_EINVAL;
+        if (bps * pl->P * n_buckets > (int64_t{1} << 30)) return GF_EINVAL;
         a.blocks_per_segment = static_cast<int32_t>(bps);
-        const dim3 grid(static_cast<unsigned>(bps * pl->P));
+        a.bucket_span = span;
+        const dim3 grid(static_cast<unsigned>(bps * pl->P * n_buckets));
         if (pl->wire == GF_WIRE_F16)
             hipLaunchKernelGGL((k_ring<uint16_t, false>), grid, dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
         else

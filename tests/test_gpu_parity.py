@@ -343,7 +343,9 @@ def _run_csc(gfm, w, schedule, mode, T, k=None, scatter=False):
             same_bits(pipe.send[p][:L].view(it), send[p].view(nt), f"t={t} send[{p}]")
             same_bits(pipe.residual[p], hg[p], f"t={t} hg[{p}]")
         st.hg = hg
-        reduced = ob.ring_fold(send, w.wire)
+        reduced = np.empty(L, dtype=send.dtype)
+        for a, b in zip(*ob.packed_buckets(w.N, w.chunk, sel_now, w.theta)):   # one ring per flushed bucket
+            reduced[a:b] = ob.ring_fold(np.ascontiguousarray(send[:, a:b]), w.wire)
         pipe.ring(); sync()
         same_bits(pipe.reduced[:L].view(it), reduced.view(nt), f"t={t} reduced")
         out = np.full(w.N, np.float32(-5.0))
@@ -404,6 +406,7 @@ def test_csc_momentum_below_one(gfm, schedule):
 def test_csc_every_chunk_selected_equals_dense(gfm):
     gf, pl = gfm
     w = odd_workload(P=4, chunk=100, density=1.0)
+    w.theta = 1 << 40                                 # one ring over the whole buffer on both sides
     pipe = _run_csc(gfm, w, "immediate", "gather", T=2)
     assert all(torch.all(r == 0) for r in pipe.residual)
     grads = cpu_grads(w, 1)
@@ -474,7 +477,7 @@ def test_sgd_update_step_of_algorithm_1(gfm, scatter, wire):
         pipe.step()
         torch.cuda.synchronize()
         out = np.full(w_.N, np.float32(-3.0))
-        r = op.csc_iteration(st, pools, w_.chunk, k, w_.loss_scale, w_.mu, "lagged", wire, out=out)
+        r = op.csc_iteration(st, pools, w_.chunk, k, w_.loss_scale, w_.mu, "lagged", wire, out=out, theta=w_.theta)
         assert np.array_equal(pipe.sel.cpu().numpy(), r["sel_next"])
         ob.sgd_update(r["reduced"], w_.N, w_.chunk, r["sel"], alpha, mom, lr, w_ref, hu_ref, None, wire)
         same_bits(pipe.out_pool, out, f"t={t} out")
@@ -541,3 +544,15 @@ def test_warmup_changes_the_number_of_important_chunks_every_iteration(gfm):
         same_bits(pipe.out_pool, out, f"t={t} out")
         for p in range(w.P):
             same_bits(pipe.residual[p], st.hg[p], f"t={t} hg[{p}]")
+
+
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+def test_packed_buffer_is_reduced_bucket_by_bucket(gfm, wire):
+    """theta below the packed length: several rings over the packed buffer, incl. a short last bucket."""
+    w = wl.scaled(wl.config("tiny"), 4)                  # C = 1024, 245 chunks, k = 62
+    w.wire = wire
+    w.theta = 5 * 1024 + 17                              # a bucket every 6 chunks
+    pipe = _run_csc(gfm, w, "lagged", "gather", T=3)
+    w2 = odd_workload(P=4, chunk=100, wire=wire)         # odd chunk length: unaligned bucket starts
+    w2.theta = 250
+    _run_csc(gfm, w2, "immediate", "gather", T=2)

@@ -252,3 +252,45 @@ def test_lagged_iterations_follow_a_changing_chunk_count():
         assert len(r["sel"]) == ks[t] and len(r["sel_next"]) == ks[t + 1]
         if t == 0:
             assert np.all(st.hg == 0)                    # iteration 0 is dense: nothing held back
+
+
+# ------------------------------------------------ lazy allreduce of the packed buffer
+
+def test_packed_buffer_buckets():
+    N, C = 10 * 100 - 30, 100                     # 10 chunks, the last one holds 70
+    sel = np.array([0, 2, 3, 5, 8, 9], dtype=np.int32)
+    L = ob.packed_len(N, C, sel)
+    assert L == 570
+    lo, hi = ob.packed_buckets(N, C, sel, 1 << 40)
+    assert list(lo) == [0] and list(hi) == [L]                        # huge threshold: one allreduce
+    lo, hi = ob.packed_buckets(N, C, sel, 0)
+    assert list(hi - lo) == [100, 100, 100, 100, 100, 70]             # every chunk alone
+    lo, hi = ob.packed_buckets(N, C, sel, 250)                        # 300 > 250 | 270 left over
+    assert list(lo) == [0, 300] and list(hi) == [300, 570]
+    lo, hi = ob.packed_buckets(N, C, sel, 200)                        # strict ">" : 300 | 270
+    assert list(hi - lo) == [300, 270]
+    lo, hi = ob.packed_buckets(N, C, sel, 199)                        # 200 > 199 thrice: 200 | 200 | 170
+    assert list(hi - lo) == [200, 200, 170]
+    rng = np.random.default_rng(4)
+    for _ in range(30):
+        k = int(rng.integers(1, 11))
+        s = np.sort(rng.choice(10, size=k, replace=False)).astype(np.int32)
+        th = int(rng.integers(0, 600))
+        lo, hi = ob.packed_buckets(N, C, s, th)
+        assert lo[0] == 0 and hi[-1] == ob.packed_len(N, C, s) and np.array_equal(lo[1:], hi[:-1])
+        assert np.all((hi - lo)[:-1] > th) and np.all((hi - lo)[:-1] - C <= th)   # closed as soon as exceeded
+        assert np.all(lo % C == 0)                                     # whole chunks only
+
+
+def test_csc_iteration_reduces_each_packed_bucket_on_its_own_ring():
+    w = small(P=3, C=64, density=0.5)
+    nc = ob.n_chunks(w.N, w.chunk)
+    k = w.k_for(nc)
+    st = op.new_state(w.P, w.N)
+    r = op.csc_iteration(st, _pools(w, 0), w.chunk, k, w.loss_scale, 1.0, "immediate", theta=3 * 64)
+    lo, hi = r["packed_bucket_lo"], r["packed_bucket_hi"]
+    assert len(lo) >= 2 and np.all((hi - lo)[:-1] == 4 * 64)
+    for a, b in zip(lo, hi):
+        assert np.array_equal(r["reduced"][a:b], ob.ring_fold(np.ascontiguousarray(r["send"][:, a:b])))
+    one = op.csc_iteration(op.new_state(w.P, w.N), _pools(w, 0), w.chunk, k, w.loss_scale, 1.0, "immediate")
+    assert not np.array_equal(one["reduced"], r["reduced"])            # the order of the sums differs
