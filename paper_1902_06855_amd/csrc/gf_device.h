@@ -52,6 +52,59 @@ __device__ __forceinline__ void gf_st_stream(T v, GF_GLOBAL T *p)
 #endif
 }
 
+// Buffer (resource-descriptor) accesses for the streaming kernels.  On this
+// part a stream of buffer_load/store_dwordx4 with the cache policy "sc0 sc1 nt"
+// sustains about 10 % more HBM bandwidth than the same stream through
+// global_load/store ... nt (measured: in-place a += b at 6.5 vs 5.9 TB/s).  The
+// descriptor also bounds every access to the run it was made for: loads beyond
+// it return zero and stores are dropped.
+#ifndef GF_AUX_STREAM
+#define GF_AUX_STREAM 19            // sc0 | nt | sc1: touched once, keep it out of the caches
+#endif
+constexpr int GF_AUX_CACHED = 0;    // default policy: data that is read again soon
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t gf_make_buf(const GF_GLOBAL void *base, uint32_t bytes)
+{
+    // Base and size are the same in every lane of a workgroup; saying so keeps the descriptor
+    // in scalar registers (otherwise each access is wrapped in a per-lane uniformity loop).
+    const uint64_t a = reinterpret_cast<uint64_t>(base);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+    const uint64_t u = (static_cast<uint64_t>(hi) << 32) | lo;
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(u), 0,
+                                             static_cast<int>(__builtin_amdgcn_readfirstlane(bytes)), 0x00020000);
+}
+template <int AUX>
+__device__ __forceinline__ gf_f32x4 gf_buf_ld128(__amdgpu_buffer_rsrc_t r, int byte_off)
+{
+    return __builtin_bit_cast(gf_f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, AUX));
+}
+template <int AUX>
+__device__ __forceinline__ gf_u32x4 gf_buf_ld128u(__amdgpu_buffer_rsrc_t r, int byte_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, AUX);
+}
+template <int AUX>
+__device__ __forceinline__ gf_u32x2 gf_buf_ld64u(__amdgpu_buffer_rsrc_t r, int byte_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, AUX);
+}
+template <int AUX>
+__device__ __forceinline__ void gf_buf_st(gf_f32x4 v, __amdgpu_buffer_rsrc_t r, int byte_off)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(gf_u32x4, v), r, byte_off, 0, AUX);
+}
+template <int AUX>
+__device__ __forceinline__ void gf_buf_st(gf_u32x4 v, __amdgpu_buffer_rsrc_t r, int byte_off)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, AUX);
+}
+template <int AUX>
+__device__ __forceinline__ void gf_buf_st(gf_u32x2 v, __amdgpu_buffer_rsrc_t r, int byte_off)
+{
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, byte_off, 0, AUX);
+}
+
 // ---- fp16 wire values travel as raw 16-bit patterns -------------------------
 // The conversions below compile to the hardware's cvt instructions, which round
 // to nearest even and keep subnormals under the default float mode of HIP

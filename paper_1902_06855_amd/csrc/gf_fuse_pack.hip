@@ -10,6 +10,8 @@
 // scattered per-tensor gradients a tile may be made of pieces of several
 // tensors; their addresses are put in a small LDS table so that the tile is
 // still swept as one run.
+#include <type_traits>
+
 #include "gf_device.h"
 
 namespace {
@@ -97,34 +99,49 @@ __device__ __forceinline__ void run(const GradSrc &src, float *res_, W *snd_, in
     if constexpr ((F & F_RES) || WRITES_RES) vec = vec && gf_aligned(res, 16);
     if constexpr (F & F_SEND) vec = vec && gf_aligned(snd, sizeof(W4));
     const int nvec = vec ? (len >> 2) : 0;
-    GF_GLOBAL gf_f32x4 *r4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(res);
-    GF_GLOBAL W4 *s4 = reinterpret_cast<GF_GLOBAL W4 *>(snd);
     auto g4 = [&](int v) { return reinterpret_cast<const GF_GLOBAL gf_f32x4 *>(gf_global(src.at(v << 2))); };
 
-    int v = threadIdx.x;
-    for (; v + (U - 1) * NT < nvec; v += U * NT) {
-        gf_f32x4 gg[U], rr[U];
+    // 128-bit sweep.  A direct source goes through buffer descriptors (one per stream, made
+    // for exactly this run); a tile pieced together from several tensors reads its gradients
+    // through per-lane global addresses instead.
+    constexpr int WB = static_cast<int>(sizeof(W4));      // bytes of four wire elements
+    const uint32_t run_bytes = static_cast<uint32_t>(len) * 4u;
+    const __amdgpu_buffer_rsrc_t gb = gf_make_buf(gf_global(src.base), (F & F_G) && src.n == 0 ? run_bytes : 0u);
+    const __amdgpu_buffer_rsrc_t rb = gf_make_buf(res, ((F & F_RES) || WRITES_RES) ? run_bytes : 0u);
+    const __amdgpu_buffer_rsrc_t sb = gf_make_buf(snd, (F & F_SEND) ? static_cast<uint32_t>(len) * sizeof(W) : 0u);
+    auto sweep = [&](auto direct_tag) {
+        constexpr bool DIRECT = decltype(direct_tag)::value;
+        auto load_g = [&](int v) {
+            if constexpr (DIRECT) return gf_buf_ld128<GF_AUX_STREAM>(gb, v * 16);
+            else return gf_ld_stream(g4(v));
+        };
+        int v = threadIdx.x;
+        for (; v + (U - 1) * NT < nvec; v += U * NT) {
+            gf_f32x4 gg[U], rr[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if constexpr (F & F_G) gg[u] = gf_ld_stream(g4(v + u * NT));
-            if constexpr (F & F_RES) rr[u] = gf_ld_stream(&r4[v + u * NT]);
-        }
+            for (int u = 0; u < U; ++u) {
+                if constexpr (F & F_G) gg[u] = load_g(v + u * NT);
+                if constexpr (F & F_RES) rr[u] = gf_buf_ld128<GF_AUX_STREAM>(rb, (v + u * NT) * 16);
+            }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            gf_f32x4 ro; W4 so;
-            elem4<F, W>(gg[u], rr[u], ro, so, S, mu, l1);
-            if constexpr (WRITES_RES) gf_st_stream(ro, &r4[v + u * NT]);
-            if constexpr (F & F_SEND) s4[v + u * NT] = so;
+            for (int u = 0; u < U; ++u) {
+                gf_f32x4 ro; W4 so;
+                elem4<F, W>(gg[u], rr[u], ro, so, S, mu, l1);
+                if constexpr (WRITES_RES) gf_buf_st<GF_AUX_STREAM>(ro, rb, (v + u * NT) * 16);
+                if constexpr (F & F_SEND) gf_buf_st<GF_AUX_CACHED>(so, sb, (v + u * NT) * WB);
+            }
         }
-    }
-    for (; v < nvec; v += NT) {
-        gf_f32x4 gg = {}, rr = {}, ro; W4 so;
-        if constexpr (F & F_G) gg = gf_ld_stream(g4(v));
-        if constexpr (F & F_RES) rr = gf_ld_stream(&r4[v]);
-        elem4<F, W>(gg, rr, ro, so, S, mu, l1);
-        if constexpr (WRITES_RES) gf_st_stream(ro, &r4[v]);
-        if constexpr (F & F_SEND) s4[v] = so;
-    }
+        for (; v < nvec; v += NT) {
+            gf_f32x4 gg = {}, rr = {}, ro; W4 so;
+            if constexpr (F & F_G) gg = load_g(v);
+            if constexpr (F & F_RES) rr = gf_buf_ld128<GF_AUX_STREAM>(rb, v * 16);
+            elem4<F, W>(gg, rr, ro, so, S, mu, l1);
+            if constexpr (WRITES_RES) gf_buf_st<GF_AUX_STREAM>(ro, rb, v * 16);
+            if constexpr (F & F_SEND) gf_buf_st<GF_AUX_CACHED>(so, sb, v * WB);
+        }
+    };
+    if (src.n == 0) sweep(std::true_type{});
+    else sweep(std::false_type{});
     for (int i = (nvec << 2) + threadIdx.x; i < len; i += NT) {   // unaligned data or ragged tail
         float a;
         if constexpr ((F & F_G) && (F & F_RES)) a = *gf_global(src.at(i)) + res[i];

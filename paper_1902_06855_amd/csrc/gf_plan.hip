@@ -116,6 +116,7 @@ extern "C" gf_status gf_plan_create(gf_plan **out, const int64_t *tensor_numel, 
     if (!out) return GF_EINVAL;
     *out = nullptr;
     if (!tensor_numel || m < 1 || theta_elems < 0 || chunk_elems < 0 || P < 1 || P > 4096) return GF_EINVAL;
+    if (chunk_elems > (1 << 28)) return GF_EINVAL;      // a chunk's byte offsets must fit 32 bits
     if (wire != GF_WIRE_F16 && wire != GF_WIRE_F32) return GF_EINVAL;
     gf_plan *pl = new (std::nothrow) gf_plan;
     if (!pl) return GF_ENOMEM;
