@@ -227,7 +227,7 @@ def main() -> int:
     for nm in [x for x in a.others.split(",") if x and x != a.workload]:
         wo = wl.config(nm)
         so = max(10, wo.iterations)
-        r = run_gpu(nm, so, 5, a.input, a.schedule, 4 if wo.chunk else 2, None, a.stage_times)
+        r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2, None, a.stage_times)
         others[nm] = {kk: r[kk] for kk in ("P", "N", "schedule", "n_buckets", "ms_per_step", "gbs", "payload_gbs",
                                             "stage_ms", "dominant", "dominant_ms")}
         others[nm]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS

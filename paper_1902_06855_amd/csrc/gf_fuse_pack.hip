@@ -284,7 +284,7 @@ gf_status launch(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
 #else
     if constexpr (MODE == MODE_DENSE) return launch_shape<MODE, 512, 4, 0>(pl, a, st);
     if (pl->tile > 16384) return launch_shape<MODE, 1024, 8, 0>(pl, a, st);
-    return launch_shape<MODE, 256, 4, 2>(pl, a, st);
+    return launch_shape<MODE, 256, 8, 2>(pl, a, st);
 #endif
 }
 

@@ -13,15 +13,9 @@
 namespace {
 
 // A dense plan's send buffers (P * N wire elements) are far larger than the
-// caches and are read exactly once: stream them.  The packed buffer of a CSC
-// plan was written just before by gf_fuse_pack and is still cache-resident:
+// caches and are read exactly once: they are streamed.  The packed buffer of a
+// CSC plan was written just before by gf_fuse_pack and is still cache-resident:
 // ordinary loads.
-template <bool STREAM, typename T>
-__device__ __forceinline__ T ring_ld(const GF_GLOBAL T *p)
-{
-    if constexpr (STREAM) return __builtin_nontemporal_load(p);
-    else return *p;
-}
 
 struct RingArgs {
     const void *const *send;
@@ -100,8 +94,20 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
         for (int q = 0; q < P; ++q) mis |= static_cast<unsigned>(reinterpret_cast<uintptr_t>(a.allgather[q]) & 15);
 
     if (mis == 0 && n == A) {
+        // Buffer descriptors anchored at this workgroup's first element: the base is uniform,
+        // each lane adds 16 bytes times its index, and nothing past the segment is reachable.
+        constexpr int AUX = DENSE ? GF_AUX_STREAM : GF_AUX_CACHED;
+        const int64_t blk = seg_lo + static_cast<int64_t>(bis) * GF_RING_GROUPS_PER_BLOCK * A;
+        const int64_t left = (seg_hi - blk) * static_cast<int64_t>(sizeof(W));
+        const uint32_t bytes = left < GF_RING_GROUPS_PER_BLOCK * 16 ? static_cast<uint32_t>(left)
+                                                                    : GF_RING_GROUPS_PER_BLOCK * 16u;
+        const int off = threadIdx.x * 16;
+        auto ld = [&](int q) {
+            const __amdgpu_buffer_rsrc_t r = gf_make_buf(gf_global(static_cast<const W *>(a.send[q])) + blk, bytes);
+            return __builtin_bit_cast(V, gf_buf_ld128u<AUX>(r, off));
+        };
         int q = s;
-        V v = ring_ld<DENSE>(reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e));
+        V v = ld(q);
         int j = 1;
         constexpr int U = 8;
         for (; j + U - 1 < P; j += U) {
@@ -109,18 +115,21 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 q = q + 1 == P ? 0 : q + 1;
-                x[u] = ring_ld<DENSE>(reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e));
+                x[u] = ld(q);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) v = hop16(v, x[u]);
         }
         for (; j < P; ++j) {
             q = q + 1 == P ? 0 : q + 1;
-            v = hop16(v, ring_ld<DENSE>(reinterpret_cast<const GF_GLOBAL V *>(gf_global(static_cast<const W *>(a.send[q])) + e)));
+            v = hop16(v, ld(q));
         }
-        *reinterpret_cast<GF_GLOBAL V *>(gf_global(static_cast<W *>(a.reduced)) + e) = v;
+        gf_buf_st<GF_AUX_CACHED>(__builtin_bit_cast(gf_u32x4, v),
+                                 gf_make_buf(gf_global(static_cast<W *>(a.reduced)) + blk, bytes), off);
         if (a.allgather)
-            for (int r = 0; r < P; ++r) *reinterpret_cast<GF_GLOBAL V *>(gf_global(static_cast<W *>(a.allgather[r])) + e) = v;
+            for (int r = 0; r < P; ++r)
+                gf_buf_st<GF_AUX_STREAM>(__builtin_bit_cast(gf_u32x4, v),
+                                         gf_make_buf(gf_global(static_cast<W *>(a.allgather[r])) + blk, bytes), off);
     } else {
         for (int i = 0; i < n; ++i) {
             int q = s;

@@ -39,10 +39,19 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
     bool vec = gf_aligned(src, sizeof(W4)) && (!dst || gf_aligned(dst, 16));
     if constexpr (UPD) vec = vec && gf_aligned(hu, 16) && gf_aligned(w, 16);
     const int nvec = vec ? (len >> 2) : 0;
-    const GF_GLOBAL W4 *s4 = reinterpret_cast<const GF_GLOBAL W4 *>(src);
-    GF_GLOBAL gf_f32x4 *d4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(dst);
-    GF_GLOBAL gf_f32x4 *h4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(hu);
-    GF_GLOBAL gf_f32x4 *w4 = reinterpret_cast<GF_GLOBAL gf_f32x4 *>(w);
+    // Streams go through buffer descriptors made for exactly this run: the reduced values were
+    // just written by the ring kernel (cached loads); everything written here is not read again
+    // in this iteration (streaming stores), as are the one-touch loads of hu and w.
+    constexpr int WB = static_cast<int>(sizeof(W4));
+    const uint32_t n4 = static_cast<uint32_t>(len) * 4u;
+    const __amdgpu_buffer_rsrc_t sb = gf_make_buf(src, static_cast<uint32_t>(len) * sizeof(W));
+    const __amdgpu_buffer_rsrc_t db = gf_make_buf(dst, dst ? n4 : 0u);
+    const __amdgpu_buffer_rsrc_t hb = gf_make_buf(hu, UPD ? n4 : 0u);
+    const __amdgpu_buffer_rsrc_t wb = gf_make_buf(w, UPD ? n4 : 0u);
+    auto ld_src = [&](int v) {
+        if constexpr (sizeof(W) == 2) return gf_buf_ld64u<GF_AUX_CACHED>(sb, v * WB);
+        else return gf_buf_ld128<GF_AUX_CACHED>(sb, v * WB);
+    };
 
     auto one = [&](int v, W4 x, gf_f32x4 hh, gf_f32x4 ww) {
         float g0, g1, g2, g3;
@@ -50,13 +59,13 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
         g0 *= alpha; g1 *= alpha; g2 *= alpha; g3 *= alpha;
         l1 += static_cast<double>(fabsf(g0)); l1 += static_cast<double>(fabsf(g1));
         l1 += static_cast<double>(fabsf(g2)); l1 += static_cast<double>(fabsf(g3));
-        if (dst) gf_st_stream(gf_pack4(g0, g1, g2, g3), &d4[v]);
+        if (dst) gf_buf_st<GF_AUX_STREAM>(gf_pack4(g0, g1, g2, g3), db, v * 16);
         if constexpr (UPD) {
             // every product and sum rounds on its own (no contraction)
             const gf_f32x4 hn = gf_pack4(mom * hh.x + lr * g0, mom * hh.y + lr * g1,
                                          mom * hh.z + lr * g2, mom * hh.w + lr * g3);
-            gf_st_stream(hn, &h4[v]);
-            gf_st_stream(gf_pack4(ww.x + hn.x, ww.y + hn.y, ww.z + hn.z, ww.w + hn.w), &w4[v]);
+            gf_buf_st<GF_AUX_STREAM>(hn, hb, v * 16);
+            gf_buf_st<GF_AUX_STREAM>(gf_pack4(ww.x + hn.x, ww.y + hn.y, ww.z + hn.z, ww.w + hn.w), wb, v * 16);
         }
     };
 
@@ -67,16 +76,19 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
         gf_f32x4 hh[U] = {}, ww[U] = {};
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            x[u] = s4[v + u * NT];
-            if constexpr (UPD) { hh[u] = gf_ld_stream(&h4[v + u * NT]); ww[u] = gf_ld_stream(&w4[v + u * NT]); }
+            x[u] = ld_src(v + u * NT);
+            if constexpr (UPD) {
+                hh[u] = gf_buf_ld128<GF_AUX_STREAM>(hb, (v + u * NT) * 16);
+                ww[u] = gf_buf_ld128<GF_AUX_STREAM>(wb, (v + u * NT) * 16);
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) one(v + u * NT, x[u], hh[u], ww[u]);
     }
     for (; v < nvec; v += NT) {
         gf_f32x4 hh = {}, ww = {};
-        if constexpr (UPD) { hh = gf_ld_stream(&h4[v]); ww = gf_ld_stream(&w4[v]); }
-        one(v, s4[v], hh, ww);
+        if constexpr (UPD) { hh = gf_buf_ld128<GF_AUX_STREAM>(hb, v * 16); ww = gf_buf_ld128<GF_AUX_STREAM>(wb, v * 16); }
+        one(v, ld_src(v), hh, ww);
     }
     for (int i = (nvec << 2) + threadIdx.x; i < len; i += NT) {
         const float g = gf_from_wire<W>(src[i]) * alpha;
