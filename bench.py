@@ -63,6 +63,8 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     w = wl.config(name)
     if chunk:                      # tuning aid: same tensors, another chunk size
         w.chunk = int(chunk)
+    if os.environ.get("GF_BENCH_P"):   # tuning aid: another worker count
+        w.P = int(os.environ["GF_BENCH_P"])
     torch.cuda.set_device(0)
     sig = wl.sigma_table(w)
     pipe_k = 0

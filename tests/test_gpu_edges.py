@@ -103,3 +103,16 @@ def test_pool_beyond_two_to_the_31_elements(gfm):
     assert np.array_equal(pipe.reduced[tidx].cpu().numpy().view(np.uint16), send)      # P = 1: identity
     out = ob.unpack_dense(send, np.float32(1) / np.float32(w.loss_scale))
     assert np.array_equal(pipe.out_pool[tidx].cpu().numpy().view(np.uint32), out.view(np.uint32))
+
+
+@pytest.mark.parametrize("chunk", [4096, 8192, 16384])
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+def test_short_power_of_two_chunks_swept_several_at_a_time(gfm, chunk, mode):
+    """Chunks of 4096 / 8192 / 16384 elements are processed several per workgroup; mixes plain
+    groups with groups that hold tensor borders, an unaligned tensor, and the ragged pool end."""
+    sizes = [chunk * 5, 100, chunk * 2 + 4, 5000, chunk * 9, 7, chunk * 3]
+    w = _wl(sizes, 3, chunk, 0.3)
+    for schedule in ("lagged", "immediate"):
+        _run_csc(gfm, w, schedule, mode, T=3)
+    w32 = _wl(sizes, 2, chunk, 0.3, wire="f32")
+    _run_csc(gfm, w32, "lagged", mode, T=2)
