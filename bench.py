@@ -43,12 +43,15 @@ def algorithmic_bytes(w, k_elems_L: int, schedule: str, sgd: bool = False):
     each output written once).  Returns (total, per-stage dict)."""
     P, N, L = w.P, w.N, k_elems_L
     ws = 2 if w.wire == "f16" else 4
-    if w.chunk == 0:
-        st = {"cast": P * N * (4 + ws), "ring": N * (P * ws + ws), "unpack": N * (ws + 4)}
+    gs = 2 if w.grad == "f16" else 4          # bytes per gradient element as it arrives
+    if w.chunk == 0 and w.extra.get("zero_copy"):
+        st = {"ring": N * (P * ws + ws), "unpack": N * (ws + 4)}
+    elif w.chunk == 0:
+        st = {"cast": P * N * (gs + ws), "ring": N * (P * ws + ws), "unpack": N * (ws + 4)}
     elif schedule == "lagged":
-        st = {"fused": P * N * 12 + P * L * ws, "ring": L * (P * ws + ws), "unpack": L * (ws + 4), "select": 0}
+        st = {"fused": P * N * (gs + 8) + P * L * ws, "ring": L * (P * ws + ws), "unpack": L * (ws + 4), "select": 0}
     else:
-        st = {"accum": P * N * 12, "pack": P * L * (4 + ws + 4), "ring": L * (P * ws + ws),
+        st = {"accum": P * N * (gs + 8), "pack": P * L * (4 + ws + 4), "ring": L * (P * ws + ws),
               "unpack": L * (ws + 4), "select": 0}
     if sgd:                                   # Algorithm 1's update step: hu and w read and written
         st["unpack"] += L * 16
@@ -74,7 +77,9 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     off, _, _ = probe_plan.layout()
     probe_plan.close()
     pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=pipe_k, mu=w.mu, wire=w.wire,
-                       schedule=schedule, sgd=sgd)
+                       schedule=schedule, sgd=sgd, grad=w.grad, zero_copy=bool(w.extra.get("zero_copy")))
+    if w.extra.get("zero_copy"):
+        mode = "pool"
     # gradient sets resident in HBM: scattered per-tensor allocations (fusion is folded into the
     # read) or one pool per worker (the zero-copy layout)
     tables, keep = [], []
@@ -87,7 +92,7 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
         else:
             pools = []
             for p in range(w.P):
-                pool = torch.empty(w.N, dtype=torch.float32, device="cuda")
+                pool = torch.empty(w.N, dtype=torch.float16 if w.grad == "f16" else torch.float32, device="cuda")
                 for l in range(w.m):
                     pool[off[l]:off[l] + w.sizes[l]] = wl.gradient_tensor(w, sig, s, p, l, "cuda")
                 pools.append(pool)
@@ -123,7 +128,7 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
         "workload": name, "P": w.P, "N": w.N, "m": w.m, "chunk": w.chunk, "k": pipe_k, "L": L,
         "schedule": schedule if w.chunk else "dense", "input": mode, "n_buckets": pipe.plan.n_buckets,
         "ms_per_step": ms_per_step, "bytes_per_step": total_bytes,
-        "gbs": total_bytes / ms_per_step / 1e6, "payload_gbs": w.P * w.N * 4 / ms_per_step / 1e6,
+        "gbs": total_bytes / ms_per_step / 1e6, "payload_gbs": w.P * w.N * (2 if w.grad == "f16" else 4) / ms_per_step / 1e6,
         "elements_per_s": w.P * w.N / ms_per_step * 1e3,
         "stage_ms": stage_avg, "stage_bytes": per_stage_bytes, "dominant": dominant,
         "dominant_ms": stage_avg.get(dominant), "gen_s": t_gen, "steps_timed": steps,
@@ -192,6 +197,9 @@ def main() -> int:
     ap.add_argument("--schedule", choices=["lagged", "immediate"], default="lagged")
     ap.add_argument("--others", default="alexnet_dense,resnet50_dense_4mb,resnet50_dense_64mb,resnet50_csc",
                     help="comma-separated extra workloads reported under config.others ('' = none)")
+    ap.add_argument("--ladder", action="store_true",
+                    help="also report the lower rungs of the ladder of Tables 1-2 (per-tensor fp32 / fp16 "
+                         "allreduce) and the fp16-input variants under config.others")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-times", action="store_true", help="bracket every stage with events (adds a few us per step)")
     ap.add_argument("--chunk", type=int, default=None, help="override the workload's chunk size (tuning aid)")
@@ -207,6 +215,8 @@ def main() -> int:
         print("bench.py: launched with WORLD_SIZE > 1; this build has no multi-GPU path", file=sys.stderr)
         return 2
     from paper_1902_06855_amd import workloads as wl
+    if a.ladder:
+        a.others = ",".join([a.others] + list(wl.LADDER_NAMES))
     w = wl.config(a.workload)
     steps = a.steps if a.steps is not None else max(10, w.iterations)
     warmup = a.warmup if a.warmup is not None else 5

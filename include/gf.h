@@ -67,11 +67,20 @@ const char *gf_status_string(gf_status s);
  * theta_elems >= 0 in wire elements.  chunk_elems = 0 makes a dense-only plan
  * (no sparsification; compute calls then work on internal fixed-size tiles and
  * the ring is run per bucket); chunk_elems >= 1 makes a CSC plan (the packed
- * buffer is reduced as one ring).  1 <= P <= 4096.
+ * buffer is reduced bucket-wise, see gf_ring_reduce_sim), at most 2^28.
+ * 1 <= P <= 4096.
  * gf_plan_create touches no GPU.  Returns GF_EINVAL / GF_ENOMEM on failure and
  * leaves *out NULL. */
 gf_status gf_plan_create(gf_plan **out, const int64_t *tensor_numel, int32_t m,
                          int64_t theta_elems, int32_t chunk_elems, int32_t P, gf_wire wire);
+
+/* Element type of the gradients handed to gf_fuse_pack (Section 3.1: the
+ * memory pool manages FP32 or FP16 gradients; Section 2.5: mixed-precision
+ * backward produces FP16 gradients).  Default GF_WIRE_F32.  With GF_WIRE_F16
+ * every pointer in `grads` / `pools` addresses IEEE binary16 values, which are
+ * widened to fp32 exactly before anything else is done to them.  Host only;
+ * may be changed between calls. */
+gf_status gf_plan_set_grad_type(gf_plan *plan, gf_wire type);
 
 /* Copies the plan's tables to the current HIP device (allocates; synchronous).
  * Required once before any compute call; idempotent. */

@@ -69,12 +69,15 @@ __device__ __forceinline__ void elem4(const gf_f32x4 g, const gf_f32x4 r, gf_f32
 //   flat:   several tensor pieces; piece i covers tile offsets
 //           [end[i-1], end[i]) and element x of the tile is at ptr[i][x].
 // In both cases `at(x)` is only evaluated for x inside the tile.
+// GT is the gradients' element type: float, or uint16_t for fp16 gradients
+// (Section 3.1: the pool holds FP32 or FP16 gradients).
+template <typename GT>
 struct GradSrc {
-    const float *base;
-    const float *const *ptr;      // LDS
+    const GT *base;
+    const GT *const *ptr;         // LDS
     const int *end;               // LDS
     int n;                        // pieces (0 = direct)
-    __device__ __forceinline__ const float *at(int x) const
+    __device__ __forceinline__ const GT *at(int x) const
     {
         if (n == 0) return base + x;
         int i = 0;
@@ -88,10 +91,11 @@ struct GradSrc {
 // and the historical gradient are touched exactly once per iteration, so they
 // go around the caches (nontemporal); the send buffer is read back by the ring
 // kernel right away and stays cacheable.
-template <int F, typename W, int NT, int U>
-__device__ __forceinline__ void run(const GradSrc &src, float *res_, W *snd_, int len, bool vec,
+template <int F, typename W, typename GT, int NT, int U>
+__device__ __forceinline__ void run(const GradSrc<GT> &src, float *res_, W *snd_, int len, bool vec,
                                     float S, float mu, double &l1)
 {
+    using G4 = typename gf_wire4<GT>::type;                // four gradients as stored
     GF_GLOBAL float *__restrict__ res = gf_global(res_);
     GF_GLOBAL W *__restrict__ snd = gf_global(snd_);
     using W4 = typename gf_wire4<W>::type;
@@ -99,21 +103,28 @@ __device__ __forceinline__ void run(const GradSrc &src, float *res_, W *snd_, in
     if constexpr ((F & F_RES) || WRITES_RES) vec = vec && gf_aligned(res, 16);
     if constexpr (F & F_SEND) vec = vec && gf_aligned(snd, sizeof(W4));
     const int nvec = vec ? (len >> 2) : 0;
-    auto g4 = [&](int v) { return reinterpret_cast<const GF_GLOBAL gf_f32x4 *>(gf_global(src.at(v << 2))); };
+    auto g4 = [&](int v) { return reinterpret_cast<const GF_GLOBAL G4 *>(gf_global(src.at(v << 2))); };
+    auto widen = [](G4 x) { float a, b, c, d; gf_unpack4(x, a, b, c, d); return gf_pack4(a, b, c, d); };
 
     // 128-bit sweep.  A direct source goes through buffer descriptors (one per stream, made
     // for exactly this run); a tile pieced together from several tensors reads its gradients
     // through per-lane global addresses instead.
     constexpr int WB = static_cast<int>(sizeof(W4));      // bytes of four wire elements
     const uint32_t run_bytes = static_cast<uint32_t>(len) * 4u;
-    const __amdgpu_buffer_rsrc_t gb = gf_make_buf(gf_global(src.base), (F & F_G) && src.n == 0 ? run_bytes : 0u);
+    constexpr int GB = static_cast<int>(sizeof(G4));      // bytes of four gradients
+    const __amdgpu_buffer_rsrc_t gb = gf_make_buf(gf_global(src.base), (F & F_G) && src.n == 0
+                                                  ? static_cast<uint32_t>(len) * sizeof(GT) : 0u);
     const __amdgpu_buffer_rsrc_t rb = gf_make_buf(res, ((F & F_RES) || WRITES_RES) ? run_bytes : 0u);
     const __amdgpu_buffer_rsrc_t sb = gf_make_buf(snd, (F & F_SEND) ? static_cast<uint32_t>(len) * sizeof(W) : 0u);
     auto sweep = [&](auto direct_tag) {
         constexpr bool DIRECT = decltype(direct_tag)::value;
         auto load_g = [&](int v) {
-            if constexpr (DIRECT) return gf_buf_ld128<GF_AUX_STREAM>(gb, v * 16);
-            else return gf_ld_stream(g4(v));
+            if constexpr (DIRECT) {
+                if constexpr (sizeof(GT) == 4) return gf_buf_ld128<GF_AUX_STREAM>(gb, v * GB);
+                else return widen(gf_buf_ld64u<GF_AUX_STREAM>(gb, v * GB));
+            } else {
+                return widen(gf_ld_stream(g4(v)));
+            }
         };
         int v = threadIdx.x;
         for (; v + (U - 1) * NT < nvec; v += U * NT) {
@@ -144,8 +155,8 @@ __device__ __forceinline__ void run(const GradSrc &src, float *res_, W *snd_, in
     else sweep(std::false_type{});
     for (int i = (nvec << 2) + threadIdx.x; i < len; i += NT) {   // unaligned data or ragged tail
         float a;
-        if constexpr ((F & F_G) && (F & F_RES)) a = *gf_global(src.at(i)) + res[i];
-        else if constexpr (F & F_G) a = *gf_global(src.at(i));
+        if constexpr ((F & F_G) && (F & F_RES)) a = gf_from_wire<GT>(*gf_global(src.at(i))) + res[i];
+        else if constexpr (F & F_G) a = gf_from_wire<GT>(*gf_global(src.at(i)));
         else a = res[i];
         if constexpr (F & F_L1) l1 += static_cast<double>(fabsf(a));
         if constexpr (F & F_SEND) snd[i] = gf_to_wire<W>(a * S);
@@ -156,64 +167,65 @@ __device__ __forceinline__ void run(const GradSrc &src, float *res_, W *snd_, in
 
 constexpr int MAX_FLAT_PIECES = 64;   // more pieces than this in one tile are walked one by one
 
-template <int F, typename W, int NT, int U>
+template <int F, typename W, typename GT, int NT, int U>
 __device__ __forceinline__ void tile_body(const FuseArgs &a, int p, int tile, int64_t slot, double &l1)
 {
+    constexpr unsigned GALIGN = 4 * sizeof(GT);            // alignment the vector path needs
     const int64_t tile_lo = static_cast<int64_t>(tile) * a.tile;
     const int64_t left = a.N - tile_lo;
     const int tile_len = left < a.tile ? static_cast<int>(left) : a.tile;
     constexpr bool USES_RES = (F & (F_RES | F_KEEP | F_ZERO)) != 0;
     float *res = USES_RES ? a.residual[p] + tile_lo : nullptr;
     W *snd = (F & F_SEND) ? static_cast<W *>(a.sendbuf[p]) + slot * a.tile : nullptr;
-    GradSrc src{nullptr, nullptr, nullptr, 0};
+    GradSrc<GT> src{nullptr, nullptr, nullptr, 0};
     if constexpr ((F & F_G) == 0) {
-        run<F, W, NT, U>(src, res, snd, tile_len, true, a.S, a.mu, l1);
+        run<F, W, GT, NT, U>(src, res, snd, tile_len, true, a.S, a.mu, l1);
         return;
     }
     if (!a.use_pieces) {
-        src.base = static_cast<const float *>(a.tab[p]) + tile_lo;
-        run<F, W, NT, U>(src, res, snd, tile_len, gf_aligned(src.base, 16), a.S, a.mu, l1);
+        src.base = static_cast<const GT *>(a.tab[p]) + tile_lo;
+        run<F, W, GT, NT, U>(src, res, snd, tile_len, gf_aligned(src.base, GALIGN), a.S, a.mu, l1);
         return;
     }
     const int ps = a.piece_start[tile], np = a.piece_start[tile + 1] - ps;
-    const float *const *tab = reinterpret_cast<const float *const *>(a.tab) + static_cast<int64_t>(p) * a.tab_stride;
+    const GT *const *tab = reinterpret_cast<const GT *const *>(a.tab) + static_cast<int64_t>(p) * a.tab_stride;
     if (np == 1) {
         const gf_piece pc = a.pieces[ps];
         src.base = tab[pc.tensor] + pc.src_off;
-        run<F, W, NT, U>(src, res, snd, tile_len, gf_aligned(src.base, 16), a.S, a.mu, l1);
+        run<F, W, GT, NT, U>(src, res, snd, tile_len, gf_aligned(src.base, GALIGN), a.S, a.mu, l1);
         return;
     }
     if (np <= MAX_FLAT_PIECES) {
         // Several tensors meet in this tile: publish where each piece lives, then
         // sweep the tile as if it were one run.
-        __shared__ const float *s_ptr[MAX_FLAT_PIECES];
+        __shared__ const GT *s_ptr[MAX_FLAT_PIECES];
         __shared__ int s_end[MAX_FLAT_PIECES];
         int misaligned = 0;
         if (static_cast<int>(threadIdx.x) < np) {
             const gf_piece pc = a.pieces[ps + threadIdx.x];
-            const float *q = tab[pc.tensor] + pc.src_off;
+            const GT *q = tab[pc.tensor] + pc.src_off;
             s_ptr[threadIdx.x] = q - pc.dst_rel;
             s_end[threadIdx.x] = pc.dst_rel + pc.len;
-            misaligned = !gf_aligned(q, 16) || (pc.dst_rel & 3);
+            misaligned = !gf_aligned(q, GALIGN) || (pc.dst_rel & 3);
         }
         const bool vec = !__syncthreads_or(misaligned);
         src.ptr = s_ptr; src.end = s_end; src.n = np;
-        run<F, W, NT, U>(src, res, snd, tile_len, vec, a.S, a.mu, l1);
+        run<F, W, GT, NT, U>(src, res, snd, tile_len, vec, a.S, a.mu, l1);
         __syncthreads();                       // the table is reused by the next caller
         return;
     }
     for (int i = ps; i < ps + np; ++i) {
         const gf_piece pc = a.pieces[i];
         src.base = tab[pc.tensor] + pc.src_off;
-        run<F, W, NT, U>(src, USES_RES ? res + pc.dst_rel : nullptr, (F & F_SEND) ? snd + pc.dst_rel : nullptr,
-                         pc.len, gf_aligned(src.base, 16), a.S, a.mu, l1);
+        run<F, W, GT, NT, U>(src, USES_RES ? res + pc.dst_rel : nullptr, (F & F_SEND) ? snd + pc.dst_rel : nullptr,
+                         pc.len, gf_aligned(src.base, GALIGN), a.S, a.mu, l1);
     }
 }
 
 // One workgroup per (worker, tile).  WPE caps the wavefronts resident per SIMD
 // (0 = no cap): fewer resident workgroups mean fewer DRAM pages open at once,
 // which the in-place read-read-write stream of short tiles rewards.
-template <int MODE, typename W, int NT, int U, int WPE>
+template <int MODE, typename W, typename GT, int NT, int U, int WPE>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE ? WPE : 1, WPE ? WPE : 8)))
 void k_fuse(const FuseArgs a)
 {
@@ -227,15 +239,15 @@ void k_fuse(const FuseArgs a)
         if (a.slotmap) slot = a.slotmap[tile];
     }
     double l1 = 0.0;
-    if constexpr (MODE == MODE_ACCUM) tile_body<F_G | F_RES | F_KEEP | F_L1, W, NT, U>(a, p, tile, 0, l1);   // mu = 1 here
+    if constexpr (MODE == MODE_ACCUM) tile_body<F_G | F_RES | F_KEEP | F_L1, W, GT, NT, U>(a, p, tile, 0, l1);   // mu = 1 here
     if constexpr (MODE == MODE_FUSED) {
-        if (slot >= 0) tile_body<F_G | F_RES | F_SEND | F_ZERO | F_L1, W, NT, U>(a, p, tile, slot, l1);
-        else tile_body<F_G | F_RES | F_KEEP | F_L1, W, NT, U>(a, p, tile, 0, l1);
+        if (slot >= 0) tile_body<F_G | F_RES | F_SEND | F_ZERO | F_L1, W, GT, NT, U>(a, p, tile, slot, l1);
+        else tile_body<F_G | F_RES | F_KEEP | F_L1, W, GT, NT, U>(a, p, tile, 0, l1);
     }
-    if constexpr (MODE == MODE_DENSE) tile_body<F_G | F_SEND, W, NT, U>(a, p, tile, slot, l1);
-    if constexpr (MODE == MODE_PACK) tile_body<F_RES | F_SEND | F_ZERO, W, NT, U>(a, p, tile, slot, l1);
+    if constexpr (MODE == MODE_DENSE) tile_body<F_G | F_SEND, W, GT, NT, U>(a, p, tile, slot, l1);
+    if constexpr (MODE == MODE_PACK) tile_body<F_RES | F_SEND | F_ZERO, W, GT, NT, U>(a, p, tile, slot, l1);
     if constexpr (MODE == MODE_SCALE) {
-        if (slot < 0) tile_body<F_RES | F_KEEP, W, NT, U>(a, p, tile, 0, l1);
+        if (slot < 0) tile_body<F_RES | F_KEEP, W, GT, NT, U>(a, p, tile, 0, l1);
     }
     if constexpr (MODE == MODE_ACCUM || MODE == MODE_FUSED) {
         const double s = gf_block_sum<NT>(l1);
@@ -264,8 +276,19 @@ gf_status launch_shape(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
     const int64_t blocks = static_cast<int64_t>(a.units) * pl->P;
     if (blocks <= 0) return GF_OK;
     const dim3 grid(static_cast<unsigned>(blocks)), block(NT);
-    if (pl->wire == GF_WIRE_F16) hipLaunchKernelGGL((k_fuse<MODE, uint16_t, NT, U, WPE>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((k_fuse<MODE, float, NT, U, WPE>), grid, block, 0, st, a);
+    // fp16 gradients only matter to the modes that read gradients
+    constexpr bool READS_G = MODE == MODE_ACCUM || MODE == MODE_FUSED || MODE == MODE_DENSE;
+    const bool f16 = pl->wire == GF_WIRE_F16;
+    if (READS_G && pl->grad == GF_WIRE_F16) {
+        if constexpr (READS_G) {
+            if (f16) hipLaunchKernelGGL((k_fuse<MODE, uint16_t, uint16_t, NT, U, WPE>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((k_fuse<MODE, float, uint16_t, NT, U, WPE>), grid, block, 0, st, a);
+        }
+    } else if (f16) {
+        hipLaunchKernelGGL((k_fuse<MODE, uint16_t, float, NT, U, WPE>), grid, block, 0, st, a);
+    } else {
+        hipLaunchKernelGGL((k_fuse<MODE, float, float, NT, U, WPE>), grid, block, 0, st, a);
+    }
     GF_LAUNCH_CHECK();
     return GF_OK;
 }

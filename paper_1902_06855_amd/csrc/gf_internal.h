@@ -48,6 +48,7 @@ struct gf_plan {
     int32_t m = 0, P = 0, chunk = 0, tile = 0, n_tiles = 0, n_chunks = 0;
     int64_t N = 0, theta = 0;
     gf_wire wire = GF_WIRE_F16;
+    gf_wire grad = GF_WIRE_F32;                  // element type of the gradients handed to gf_fuse_pack
     std::vector<int64_t> numel, off;             // ID order
     std::vector<int64_t> bucket_lo, bucket_hi;   // generation order
     std::vector<int32_t> piece_start;            // [n_tiles + 1]

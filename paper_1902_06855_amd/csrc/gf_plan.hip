@@ -242,3 +242,11 @@ extern "C" int32_t gf_plan_warmup_k(const gf_plan *pl, double final_density, int
     if (k > pl->n_chunks) k = pl->n_chunks;
     return static_cast<int32_t>(k);
 }
+
+// Section 3.1: the pool may hold FP16 gradients (mixed-precision backward).
+extern "C" gf_status gf_plan_set_grad_type(gf_plan *pl, gf_wire type)
+{
+    if (!pl || (type != GF_WIRE_F16 && type != GF_WIRE_F32)) return GF_EINVAL;
+    pl->grad = type;
+    return GF_OK;
+}

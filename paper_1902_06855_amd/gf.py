@@ -32,7 +32,7 @@ GF_WIRE_F16, GF_WIRE_F32 = 0, 1
 GF_PHASE_ACCUM, GF_PHASE_PACK = 1, 2
 
 EXPORTS = (
-    "gf_status_string", "gf_plan_create", "gf_plan_to_device", "gf_plan_destroy", "gf_plan_info",
+    "gf_status_string", "gf_plan_create", "gf_plan_set_grad_type", "gf_plan_to_device", "gf_plan_destroy", "gf_plan_info",
     "gf_plan_layout", "gf_plan_ring_segment", "gf_plan_tiles", "gf_plan_tile_pieces",
     "gf_plan_workspace_bytes", "gf_plan_warmup_k", "gf_fuse_pack", "gf_chunk_score_select", "gf_ring_reduce_sim",
     "gf_unpack_apply", "gf_unpack_sgd_update",
@@ -51,6 +51,7 @@ def _sig(name, restype, *argtypes):
 _status_string = _sig("gf_status_string", C.c_char_p, C.c_int)
 _plan_create = _sig("gf_plan_create", C.c_int, C.POINTER(_vp), C.POINTER(_i64), _i32, _i64, _i32, _i32, C.c_int)
 _plan_to_device = _sig("gf_plan_to_device", C.c_int, _vp)
+_plan_set_grad_type = _sig("gf_plan_set_grad_type", C.c_int, _vp, C.c_int)
 _plan_destroy = _sig("gf_plan_destroy", None, _vp)
 _plan_info = _sig("gf_plan_info", C.c_int, _vp, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_i32))
 _plan_layout = _sig("gf_plan_layout", C.c_int, _vp, C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64))
@@ -129,6 +130,10 @@ class Plan:
 
     def to_device(self) -> None:
         _check(_plan_to_device(self.handle), "gf_plan_to_device")
+
+    def set_grad_type(self, wire: int) -> None:
+        """GF_WIRE_F16: the gradients given to gf_fuse_pack are fp16; GF_WIRE_F32 (default): fp32."""
+        _check(_plan_set_grad_type(self.handle, int(wire)), "gf_plan_set_grad_type")
 
     def layout(self) -> Tuple[List[int], List[int], List[int]]:
         off = (_i64 * self.m)()

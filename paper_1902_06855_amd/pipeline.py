@@ -11,7 +11,10 @@ Schedules for a plan with chunks (coarse-grained sparse communication):
                phases).  Iteration 0 chooses from its own accumulated gradients.
   "immediate"  every iteration chooses from its own accumulated gradients:
                accumulate pass, select, pack pass.
-A dense plan (chunk = 0) runs cast -> per-bucket ring -> cast back.
+A dense plan (chunk = 0) runs cast -> per-bucket ring -> cast back.  With fp16
+pools as input and `zero_copy` set, the cast pass is dropped: the ring reads
+the workers' pools in place (the memory pool of Section 3.1 holding fp16
+gradients, reduced bucket by bucket with no copy).
 """
 from __future__ import annotations
 
@@ -27,14 +30,20 @@ class Pipeline:
     def __init__(self, sizes: Sequence[int], P: int, chunk: int, theta: int, loss_scale: float,
                  k: int = 0, mu: float = 1.0, wire: str = "f16", schedule: str = "lagged",
                  scatter_out: bool = False, allgather: bool = False, device: str = "cuda",
-                 sgd: Optional[tuple] = None, k_max: Optional[int] = None):
+                 sgd: Optional[tuple] = None, k_max: Optional[int] = None, grad: str = "f32",
+                 zero_copy: bool = False):
         assert schedule in ("lagged", "immediate")
+        if zero_copy and not (chunk == 0 and grad == "f16" and wire == "f16"):
+            raise ValueError("zero_copy needs a dense plan with fp16 pools on an fp16 wire")
+        self.zero_copy = bool(zero_copy)
         self.sizes, self.P, self.chunk, self.mu = list(sizes), int(P), int(chunk), float(mu)
         self.S, self.schedule, self.device = float(loss_scale), schedule, device
         self.alpha = float(np.float32(1.0) / np.float32(loss_scale))   # 1/S rounded once to fp32
         self.wire = gf.GF_WIRE_F16 if wire == "f16" else gf.GF_WIRE_F32
         self.wdtype = torch.float16 if wire == "f16" else torch.float32
         self.plan = gf.Plan(self.sizes, min(int(theta), 1 << 60), self.chunk, self.P, self.wire)
+        if grad == "f16":                      # gradients arrive as fp16 (mixed-precision backward)
+            self.plan.set_grad_type(gf.GF_WIRE_F16)
         self.N, self.n_chunks, self.m = self.plan.N, self.plan.n_chunks, len(self.sizes)
         # k: important chunks in the current selection; k_next: how many the next selection
         # takes (warm-up changes it between iterations); buffers are sized for k_max
@@ -57,8 +66,10 @@ class Pipeline:
         else:
             self.cap_max = self.N
             self.residual = None
-        self.send = [new(self.cap_max, self.wdtype) for _ in range(self.P)]
-        self.send_tab = gf.ptr_table(self.send, device)
+        self.send, self.send_tab = None, None
+        if not self.zero_copy:
+            self.send = [new(self.cap_max, self.wdtype) for _ in range(self.P)]
+            self.send_tab = gf.ptr_table(self.send, device)
         self.reduced = new(self.cap_max, self.wdtype)
         self.out_pool = new(self.N, torch.float32)
         self.out_tensors = self.out_tab = None
@@ -143,7 +154,10 @@ class Pipeline:
             gf.gf_ring_reduce_sim(self.plan, self.send_tab, self.cap, self.reduced, L_dev=self.packed_len,
                                   allgather_out=self.ag_tab, workspace=self.ws)
         else:
-            gf.gf_ring_reduce_sim(self.plan, self.send_tab, self.N, self.reduced, allgather_out=self.ag_tab,
+            src = self.pools_tab if self.zero_copy else self.send_tab
+            if src is None:
+                raise ValueError("zero_copy reduces pools in place: call set_pools first")
+            gf.gf_ring_reduce_sim(self.plan, src, self.N, self.reduced, allgather_out=self.ag_tab,
                                   workspace=self.ws)
 
     def unpack(self) -> None:
@@ -178,7 +192,9 @@ class Pipeline:
     def step(self) -> None:
         """One whole iteration on the current stream; returns without synchronising."""
         if not self.chunk:
-            self._run("cast", self.cast_dense); self._run("ring", self.ring); self._run("unpack", self.unpack)
+            if not self.zero_copy:
+                self._run("cast", self.cast_dense)
+            self._run("ring", self.ring); self._run("unpack", self.unpack)
         elif self.schedule == "immediate" or self.t == 0:
             self._run("accum", self.accum); self._run("select", self.select, False)
             self._run("pack", self.pack); self._run("ring", self.ring); self._run("unpack", self.unpack)

@@ -74,6 +74,7 @@ class Workload:
     seed: int = 1902_06855
     wire: str = "f16"
     extra: dict = field(default_factory=dict)
+    grad: str = "f32"              # element type the gradients arrive in
 
     @property
     def m(self) -> int:
@@ -92,7 +93,10 @@ MB = 1 << 20
 
 
 def config(name: str) -> Workload:
-    """The five configurations this build is measured and checked on."""
+    """The configurations this build is measured and checked on, and the rungs
+    below them of the ladder of Tables 1-2 (one allreduce per tensor in fp32,
+    the same in fp16, then lazy allreduce, then sparse communication), plus the
+    fp16-resident pool of Section 3.1 reduced in place."""
     if name == "tiny":
         return Workload("tiny", tiny_sizes(), P=4, chunk=4096, density=0.25,
                         loss_scale=1024.0, theta=1 << 40)
@@ -111,8 +115,24 @@ def config(name: str) -> Workload:
     if name == "resnet50_csc":
         return Workload("resnet50_csc", resnet50_sizes(), P=64, chunk=8192, density=0.01,
                         loss_scale=128.0, theta=1 << 40, iterations=20)
+    base = {"alexnet": (alexnet_sizes, 1024.0), "resnet50": (resnet50_sizes, 128.0)}
+    for net, (sizes, S) in base.items():
+        if name == net + "_pertensor_fp32":    # baseline: every tensor its own fp32 allreduce
+            return Workload(name, sizes(), P=8, chunk=0, density=1.0, loss_scale=1.0, theta=0, wire="f32")
+        if name == net + "_pertensor_fp16":    # + mixed precision
+            return Workload(name, sizes(), P=8, chunk=0, density=1.0, loss_scale=S, theta=0)
+        if name == net + "_fp16pool":          # fp16 gradients already in the pool, reduced in place
+            return Workload(name, sizes(), P=8, chunk=0, density=1.0, loss_scale=S, theta=32 * MB // 2,
+                            grad="f16", extra={"zero_copy": True})
+    if name == "alexnet_csc_fp16in":           # sparse path fed with fp16 gradients
+        w = config("alexnet_csc")
+        w.name, w.grad = name, "f16"
+        return w
     raise KeyError(name)
 
+
+LADDER_NAMES = ("alexnet_pertensor_fp32", "alexnet_pertensor_fp16", "alexnet_fp16pool", "alexnet_csc_fp16in",
+                "resnet50_pertensor_fp32", "resnet50_pertensor_fp16", "resnet50_fp16pool")
 
 CONFIG_NAMES = ("tiny", "alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb",
                 "alexnet_csc", "resnet50_csc")
@@ -126,7 +146,7 @@ def scaled(w: Workload, divisor: int, name: Optional[str] = None) -> Workload:
     chunk = 0 if w.chunk == 0 else max(64, w.chunk // divisor)
     theta = w.theta if w.theta >= (1 << 40) else max(1, w.theta // divisor)
     return Workload(name or f"{w.name}_div{divisor}", sizes, w.P, chunk, w.density,
-                    w.loss_scale, theta, w.iterations, w.mu, w.seed, w.wire, dict(w.extra))
+                    w.loss_scale, theta, w.iterations, w.mu, w.seed, w.wire, dict(w.extra), w.grad)
 
 
 def _mix(*vals: int) -> int:
@@ -150,11 +170,13 @@ def sigma_table(w: Workload) -> np.ndarray:
 
 def gradient_tensor(w: Workload, sig: np.ndarray, t: int, p: int, l: int,
                     device: str = "cpu") -> torch.Tensor:
-    """Tensor l (0-based ID-order index) of worker p at iteration t, fp32."""
+    """Tensor l (0-based ID-order index) of worker p at iteration t, fp32 (or
+    those values converted to fp16 when the workload's gradients arrive so)."""
     g = torch.Generator(device=device)
     g.manual_seed(_mix(w.seed, t, p, l))
     x = torch.randn(w.sizes[l], generator=g, device=device, dtype=torch.float32)
-    return x.mul_(float(sig[l, p]))
+    x.mul_(float(sig[l, p]))
+    return x.to(torch.float16) if w.grad == "f16" else x
 
 
 def gradients(w: Workload, t: int, device: str = "cpu",

@@ -556,3 +556,86 @@ def test_packed_buffer_is_reduced_bucket_by_bucket(gfm, wire):
     w2 = odd_workload(P=4, chunk=100, wire=wire)         # odd chunk length: unaligned bucket starts
     w2.theta = 250
     _run_csc(gfm, w2, "immediate", "gather", T=2)
+
+
+# ------------------------------------------------------- fp16 gradients as input
+
+def _half_grads(w, t):
+    """fp16 gradients (as a mixed-precision backward would hand them over) and their exact fp32 values."""
+    g16 = [[x.to(torch.float16) for x in row] for row in cpu_grads(w, t)]
+    g32 = [[torch.from_numpy(ob.f16_to_f32(x.numpy().view(np.uint16))) for x in row] for row in g16]
+    return g16, g32
+
+
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+def test_fp16_gradients_csc(gfm, mode, wire):
+    gf, pl = gfm
+    for w in (odd_workload(P=3, chunk=96, wire=wire), wl.scaled(wl.config("tiny"), 4)):
+        w.wire = wire
+        w.theta = 1 << 40
+        nc = ob.n_chunks(w.N, w.chunk)
+        k = w.k_for(nc)
+        pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=k, wire=wire, schedule="lagged", grad="f16")
+        st = op.new_state(w.P, w.N)
+        for t in range(3):
+            g16, g32 = _half_grads(w, t)
+            if mode == "gather":
+                pipe.set_gradients(to_dev(g16))
+            else:
+                pipe.set_pools([torch.cat([x for x in reversed(row)]).cuda() for row in g16])
+            pipe.out_pool.fill_(-4.0)
+            pipe.step()
+            torch.cuda.synchronize()
+            out = np.full(w.N, np.float32(-4.0))
+            r = op.csc_iteration(st, pools_np(g32, w.sizes), w.chunk, k, w.loss_scale, w.mu, "lagged", wire, out=out)
+            assert np.array_equal(pipe.sel.cpu().numpy(), r["sel_next"]), f"t={t} selection"
+            same_bits(pipe.out_pool, out, f"t={t} out")
+            close_rel(pipe.l1, r["l1"].reshape(-1), f"t={t} norms")
+            for p in range(w.P):
+                same_bits(pipe.residual[p], st.hg[p], f"t={t} hg[{p}]")
+
+
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+def test_fp16_gradients_dense(gfm, mode):
+    gf, pl = gfm
+    w = odd_workload(P=3, chunk=0)
+    g16, g32 = _half_grads(w, 0)
+    ref = op.dense_iteration(pools_np(g32, w.sizes), w.sizes, w.theta, w.loss_scale)
+    pipe = pl.Pipeline(w.sizes, w.P, 0, w.theta, w.loss_scale, grad="f16")
+    if mode == "gather":
+        pipe.set_gradients(to_dev(g16))
+    else:
+        pipe.set_pools([torch.cat([x for x in reversed(row)]).cuda() for row in g16])
+    pipe.step()
+    torch.cuda.synchronize()
+    for p in range(w.P):
+        same_bits(pipe.send[p].view(torch.int16), ref["send"][p].view(np.int16), f"send[{p}]")
+    same_bits(pipe.out_pool, ref["out"], "out")
+
+
+@pytest.mark.parametrize("theta", [1 << 40, 700, 0])
+def test_fp16_pools_reduced_in_place(gfm, theta):
+    """fp16 pools on an fp16 wire: no cast pass, each bucket of the pools is ring-reduced where it lies."""
+    gf, pl = gfm
+    w = odd_workload(P=5, chunk=0)
+    g16, _ = _half_grads(w, 0)
+    pools = [torch.cat([x for x in reversed(row)]) for row in g16]
+    h = np.stack([x.numpy().view(np.uint16) for x in pools])
+    lo, hi = ob.buckets(w.sizes, theta)
+    reduced = np.empty(w.N, dtype=np.uint16)
+    for a, b in zip(lo, hi):
+        reduced[a:b] = ob.ring_fold(np.ascontiguousarray(h[:, a:b]), "f16")
+    out = ob.unpack_dense(reduced, np.float32(1.0) / np.float32(w.loss_scale), "f16")
+    pipe = pl.Pipeline(w.sizes, w.P, 0, theta, w.loss_scale, grad="f16", zero_copy=True)
+    assert pipe.send is None and pipe.plan.n_buckets == len(lo)
+    dev = [x.cuda() for x in pools]
+    pipe.set_pools(dev)
+    pipe.step()
+    torch.cuda.synchronize()
+    same_bits(pipe.reduced.view(torch.int16), reduced.view(np.int16), "reduced")
+    same_bits(pipe.out_pool, out, "out")
+    for p in range(w.P):                                   # the pools themselves are only read
+        assert torch.equal(dev[p].cpu().view(torch.int16), pools[p].view(torch.int16))
+    with pytest.raises(ValueError):
+        pl.Pipeline(w.sizes, w.P, 0, theta, w.loss_scale, grad="f32", zero_copy=True)
