@@ -53,6 +53,8 @@ _cast_w = _sig("gfo_cast_dense_workers", None, _i32, _vp, _i32, _i64, _f32, _vp)
 _ring_seg = _sig("gfo_ring_segment", _i64, _i64, _i32, C.c_int)
 _ring_hops = _sig("gfo_ring_allreduce_hops", None, C.c_int, _vp, _i64, _i32, _vp)
 _ring_fold = _sig("gfo_ring_fold", None, C.c_int, _vp, _i64, _i32, _vp)
+_hier_hops = _sig("gfo_hier_allreduce_hops", None, C.c_int, _vp, _i64, _i32, _i32, _vp)
+_hier_fold = _sig("gfo_hier_fold", None, C.c_int, _vp, _i64, _i32, _i32, _vp)
 _unpack = _sig("gfo_unpack", None, C.c_int, _vp, _i64, _i64, _vp, _i32, _f32, _vp, _vp)
 _sgd_update = _sig("gfo_sgd_update", None, C.c_int, _vp, _i64, _i64, _vp, _i32, _f32, _f32, _f32, _vp, _vp, _vp)
 _unpack_dense = _sig("gfo_unpack_dense", None, C.c_int, _vp, _i64, _f32, _vp)
@@ -216,6 +218,33 @@ def ring_fold(x: np.ndarray, wire: str = "f16") -> np.ndarray:
     out = np.empty(L, dtype=x.dtype)
     _ring_fold(WIRE[wire], _ptr(x), L, P, _ptr(out))
     return out
+
+
+def hier_allreduce_hops(x: np.ndarray, M: int, wire: str = "f16") -> Tuple[np.ndarray, np.ndarray]:
+    """Hierarchical allreduce with M groups of consecutive ranks, message by message:
+    x [P, L] -> (all ranks' final buffers [P, L], elements sent per rank [P])."""
+    assert x.dtype == WIRE_DTYPE[wire] and x.ndim == 2
+    buf = x.copy()
+    P, L = buf.shape
+    assert 1 <= M <= P and P % M == 0
+    sent = np.zeros(P, dtype=np.int64)
+    _hier_hops(WIRE[wire], _ptr(buf), L, P, int(M), _ptr(sent))
+    return buf, sent
+
+
+def hier_fold(x: np.ndarray, M: int, wire: str = "f16") -> np.ndarray:
+    assert x.dtype == WIRE_DTYPE[wire] and x.ndim == 2
+    x = np.ascontiguousarray(x)
+    P, L = x.shape
+    assert 1 <= M <= P and P % M == 0
+    out = np.empty(L, dtype=x.dtype)
+    _hier_fold(WIRE[wire], _ptr(x), L, P, int(M), _ptr(out))
+    return out
+
+
+def allreduce(x: np.ndarray, wire: str = "f16", groups: int = 0) -> np.ndarray:
+    """The reduced buffer [L] of x [P, L]: flat ring, or hierarchical with `groups` groups."""
+    return hier_fold(x, groups, wire) if groups else ring_fold(x, wire)
 
 
 def unpack(reduced: np.ndarray, N: int, Cc: int, sel: np.ndarray, alpha: float,

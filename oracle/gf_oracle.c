@@ -15,7 +15,10 @@
  * Parity pins (tests/test_oracle_*.py): the two casts against numpy's float16;
  * layout against the closed form of Section 3.1; buckets against hand-worked
  * lists; the hop-by-hop ring against the rotated fold, against exact integer
- * sums and against the traffic formula of Section 2.4; selection against a
+ * sums and against the traffic formula of Section 2.4; the hierarchical
+ * allreduce, message by message, against its formula, hand-worked fp16 sums
+ * that tell the chain and rotation orders apart, exact integer sums and the
+ * message size of Section 2.4; selection against a
  * full sort; residual bookkeeping against the conservation property stated
  * with Algorithm 1.  End-to-end numeric values: PARITY UNPINNED by the paper
  * (it prints no worked example); they rest on the pins above.
@@ -444,6 +447,106 @@ void gfo_ring_fold(int wire, const void *x, int64_t L, int32_t P, void *out)
                 const float *xs = (const float *)x;
                 float v = xs[(size_t)s * L + i];
                 for (int32_t j = 1; j < P; ++j) v = v + xs[(size_t)imod(s + j, P) * L + i];
+                ((float *)out)[i] = v;
+            }
+        }
+    }
+}
+
+/* ------------------------------------ hierarchical allreduce (Sec. 2.4)
+ * The P ranks form M groups of G = P / M consecutive ranks; the lowest rank of
+ * a group is its master.  Three phases: a ring-based reduce inside each group
+ * that leaves the group's sum on the master, a ring allreduce among the M
+ * masters, a broadcast inside each group.
+ *
+ * Readings where the paper gives no detail: ranks send to their successor as
+ * in the flat ring, so the reduce inside a group is a chain that starts at the
+ * rank after the master and ends on the master (each rank adds its own values
+ * to the partial sum it receives and rounds to the wire type); the broadcast is
+ * the same chain run the other way round, plain copies.  The masters' ring
+ * cuts the L elements into M segments (its message is L / M elements; the
+ * L * M / P of the text is the same number in its 16-rank, 4-group example).
+ *
+ * Message-passing emulation, buf [P][L] updated in place; sent[r] counts the
+ * elements rank r put on the wire over the three phases. */
+void gfo_hier_allreduce_hops(int wire, void *buf, int64_t L, int32_t P, int32_t M, int64_t *sent)
+{
+    size_t es = wire == 0 ? 2 : 4;
+    int32_t G = P / M;
+    unsigned char *base = (unsigned char *)buf;
+    for (int32_t r = 0; r < P; ++r) sent[r] = 0;
+
+    /* phase 1: at step t the rank at local position 1 + t hands its partial sum on */
+    for (int32_t t = 0; t + 1 < G; ++t) {
+        for (int32_t g = 0; g < M; ++g) {
+            int32_t src = g * G + 1 + t;
+            int32_t dst = g * G + (2 + t) % G;
+            sent[src] += L;
+            if (wire == 0) {
+                const uint16_t *in = (const uint16_t *)base + (size_t)src * L;
+                uint16_t *own = (uint16_t *)base + (size_t)dst * L;
+                for (int64_t i = 0; i < L; ++i) own[i] = gfo_f16_add(in[i], own[i]);
+            } else {
+                const float *in = (const float *)base + (size_t)src * L;
+                float *own = (float *)base + (size_t)dst * L;
+                for (int64_t i = 0; i < L; ++i) own[i] = in[i] + own[i];
+            }
+        }
+    }
+
+    /* phase 2: the flat ring among the masters */
+    unsigned char *mast = (unsigned char *)malloc((size_t)M * (size_t)(L ? L : 1) * es);
+    int64_t *msent = (int64_t *)malloc((size_t)M * sizeof(int64_t));
+    for (int32_t g = 0; g < M; ++g) memcpy(mast + (size_t)g * L * es, base + (size_t)g * G * L * es, (size_t)L * es);
+    gfo_ring_allreduce_hops(wire, mast, L, M, msent);
+    for (int32_t g = 0; g < M; ++g) {
+        memcpy(base + (size_t)g * G * L * es, mast + (size_t)g * L * es, (size_t)L * es);
+        sent[g * G] += msent[g];
+    }
+    free(mast);
+    free(msent);
+
+    /* phase 3: master -> local 1 -> ... -> local G - 1 */
+    for (int32_t t = 0; t + 1 < G; ++t) {
+        for (int32_t g = 0; g < M; ++g) {
+            int32_t src = g * G + t, dst = g * G + t + 1;
+            sent[src] += L;
+            memcpy(base + (size_t)dst * L * es, base + (size_t)src * L * es, (size_t)L * es);
+        }
+    }
+}
+
+/* The same result as a formula: y_g = x_{gG+1} + x_{gG+2} + ... + x_{gG+G-1} + x_{gG}
+ * (left to right), and element i of the masters' segment s is the left fold
+ * y_s + y_{s+1} + ... + y_{s-1} (indices mod M); every addition rounds to the
+ * wire type.  x is [P][L], out is [L]. */
+void gfo_hier_fold(int wire, const void *x, int64_t L, int32_t P, int32_t M, void *out)
+{
+    int32_t G = P / M;
+    int64_t seg = ring_seg(L, M, wire);
+#pragma omp parallel for schedule(static)
+    for (int32_t s = 0; s < M; ++s) {
+        int64_t lo, hi; seg_range(L, seg, s, &lo, &hi);
+        for (int64_t i = lo; i < hi; ++i) {
+            if (wire == 0) {
+                const uint16_t *xs = (const uint16_t *)x;
+                uint16_t v = 0;
+                for (int32_t j = 0; j < M; ++j) {
+                    int32_t g = imod(s + j, M);
+                    uint16_t y = xs[(size_t)(g * G + 1 % G) * L + i];
+                    for (int32_t q = 2; q <= G; ++q) y = gfo_f16_add(y, xs[(size_t)(g * G + q % G) * L + i]);
+                    v = j == 0 ? y : gfo_f16_add(v, y);
+                }
+                ((uint16_t *)out)[i] = v;
+            } else {
+                const float *xs = (const float *)x;
+                float v = 0.0f;
+                for (int32_t j = 0; j < M; ++j) {
+                    int32_t g = imod(s + j, M);
+                    float y = xs[(size_t)(g * G + 1 % G) * L + i];
+                    for (int32_t q = 2; q <= G; ++q) y = y + xs[(size_t)(g * G + q % G) * L + i];
+                    v = j == 0 ? y : v + y;
+                }
                 ((float *)out)[i] = v;
             }
         }

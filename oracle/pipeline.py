@@ -45,15 +45,16 @@ def views(pool: np.ndarray, sizes: Sequence[int]) -> List[np.ndarray]:
 
 
 def dense_iteration(pools: np.ndarray, sizes: Sequence[int], theta: int, S: float,
-                    wire: str = "f16") -> Dict[str, np.ndarray]:
-    """pools [P, N] fp32.  Lazy allreduce without sparsification: cast, one ring
-    allreduce per bucket, cast back (times 1/S)."""
+                    wire: str = "f16", groups: int = 0) -> Dict[str, np.ndarray]:
+    """pools [P, N] fp32.  Lazy allreduce without sparsification: cast, one
+    allreduce per bucket (flat ring, or hierarchical with `groups` groups), cast
+    back (times 1/S)."""
     P, N = pools.shape
     lo, hi = ob.buckets(sizes, theta)
     send = ob.cast_dense(pools, S, wire)
     reduced = np.empty(N, dtype=send.dtype)
     for a, b in zip(lo, hi):
-        reduced[a:b] = ob.ring_fold(np.ascontiguousarray(send[:, a:b]), wire)
+        reduced[a:b] = ob.allreduce(np.ascontiguousarray(send[:, a:b]), wire, groups)
     out = ob.unpack_dense(reduced, np.float32(1.0) / np.float32(S), wire)
     return dict(send=send, reduced=reduced, out=out, bucket_lo=lo, bucket_hi=hi)
 
@@ -72,14 +73,15 @@ def csc_iteration(state: CscState, pools: np.ndarray, C: int, k: int, S: float, 
                   schedule: str = "lagged", wire: str = "f16",
                   out: Optional[np.ndarray] = None, k_next: Optional[int] = None,
                   theta: int = 1 << 60,
-                  choose: Optional[Callable[[str, np.ndarray, np.ndarray], np.ndarray]] = None
-                  ) -> Dict[str, np.ndarray]:
+                  choose: Optional[Callable[[str, np.ndarray, np.ndarray], np.ndarray]] = None,
+                  groups: int = 0) -> Dict[str, np.ndarray]:
     """One iteration; updates `state` in place and returns every intermediate.
 
     k is the number of important chunks of this iteration; k_next (default k)
     is how many the lagged schedule picks for the next one (warm-up changes it
     from iteration to iteration).  theta is the lazy-allreduce threshold on the
-    packed buffer: each bucket of it is reduced by a ring allreduce of its own.
+    packed buffer: each bucket of it is reduced by an allreduce of its own
+    (the flat ring, or the hierarchical one with `groups` groups).
 
     choose(stage, score, sel) may replace a selection (stage is "pre" for one
     taken before packing, "post" for one taken after the allreduce); tests use
@@ -107,7 +109,7 @@ def csc_iteration(state: CscState, pools: np.ndarray, C: int, k: int, S: float, 
     reduced = np.empty(send.shape[1], dtype=send.dtype)
     b_lo, b_hi = ob.packed_buckets(N, C, sel, theta)
     for a, b in zip(b_lo, b_hi):
-        reduced[a:b] = ob.ring_fold(np.ascontiguousarray(send[:, a:b]), wire)
+        reduced[a:b] = ob.allreduce(np.ascontiguousarray(send[:, a:b]), wire, groups)
     r["packed_bucket_lo"], r["packed_bucket_hi"] = b_lo, b_hi
     if out is None:
         out = np.zeros(N, dtype=np.float32)
