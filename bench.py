@@ -77,7 +77,8 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     off, _, _ = probe_plan.layout()
     probe_plan.close()
     pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=pipe_k, mu=w.mu, wire=w.wire,
-                       schedule=schedule, sgd=sgd, grad=w.grad, zero_copy=bool(w.extra.get("zero_copy")))
+                       schedule=schedule, sgd=sgd, grad=w.grad, zero_copy=bool(w.extra.get("zero_copy")),
+                       groups=int(w.extra.get("groups", 0)))
     if w.extra.get("zero_copy"):
         mode = "pool"
     # gradient sets resident in HBM: scattered per-tensor allocations (fusion is folded into the

@@ -40,7 +40,9 @@ typedef enum {
     GF_EINVAL = 1,   /* bad argument (null where required, out of range, wrong mode) */
     GF_ENOMEM = 2,   /* host or device allocation failed (plan calls only)          */
     GF_EHIP = 3,     /* a HIP runtime call or kernel launch failed                  */
-    GF_ESTATE = 4    /* plan has no device tables yet (call gf_plan_to_device)      */
+    GF_ESTATE = 4    /* plan in the wrong state: device tables missing (call
+                        gf_plan_to_device), or already uploaded for a setter that
+                        must run before                                             */
 } gf_status;
 
 /* Element type of what travels between workers (Section 2.5: fp16 gradients go
@@ -81,6 +83,23 @@ gf_status gf_plan_create(gf_plan **out, const int64_t *tensor_numel, int32_t m,
  * widened to fp32 exactly before anything else is done to them.  Host only;
  * may be changed between calls. */
 gf_status gf_plan_set_grad_type(gf_plan *plan, gf_wire type);
+
+/* Order of the simulated allreduce (Section 2.4).  M = 0 or M = P: the flat
+ * ring over all P ranks (the default).  Otherwise the hierarchical allreduce
+ * with M groups of G = P / M consecutive ranks (P must be a multiple of M), the
+ * lowest rank of a group being its master:
+ *   1. ring-based reduce inside each group: the partial sum travels along the
+ *      chain that starts at the rank after the master and ends on the master,
+ *      y_g = x_{gG+1} + x_{gG+2} + ... + x_{gG+G-1} + x_{gG}, rounded to the
+ *      wire type at every hop;
+ *   2. ring allreduce among the M masters: the buffer (or bucket) is cut into M
+ *      segments of roundup(ceil(len / M), 16 bytes) elements and segment s ends
+ *      as y_s + y_{s+1} + ... + y_{s-1} (indices mod M);
+ *   3. broadcast inside each group (copies, no arithmetic).
+ * gf_ring_reduce_sim, gf_plan_ring_segment and the bucket rule are otherwise
+ * unchanged.  Host only; must be called before gf_plan_to_device (GF_ESTATE
+ * afterwards).  GF_EINVAL if M does not divide P. */
+gf_status gf_plan_set_reduce_groups(gf_plan *plan, int32_t M);
 
 /* Copies the plan's tables to the current HIP device (allocates; synchronous).
  * Required once before any compute call; idempotent. */

@@ -49,6 +49,7 @@ struct gf_plan {
     int64_t N = 0, theta = 0;
     gf_wire wire = GF_WIRE_F16;
     gf_wire grad = GF_WIRE_F32;                  // element type of the gradients handed to gf_fuse_pack
+    int32_t ring_M = 0;                          // ranks in the ring (P, or the masters of a hierarchical allreduce)
     std::vector<int64_t> numel, off;             // ID order
     std::vector<int64_t> bucket_lo, bucket_hi;   // generation order
     std::vector<int32_t> piece_start;            // [n_tiles + 1]

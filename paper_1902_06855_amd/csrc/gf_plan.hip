@@ -15,9 +15,44 @@ extern "C" const char *gf_status_string(gf_status s)
     case GF_EINVAL: return "GF_EINVAL: invalid argument";
     case GF_ENOMEM: return "GF_ENOMEM: allocation failed";
     case GF_EHIP: return "GF_EHIP: HIP runtime error";
-    case GF_ESTATE: return "GF_ESTATE: plan tables are not on the device";
+    case GF_ESTATE: return "GF_ESTATE: plan in the wrong state (tables not on the device, or already uploaded)";
     }
     return "unknown gf_status";
+}
+
+// Ring tables (Section 2.4).  A CSC plan reduces the packed buffer, whose length
+// is only known at call time; a dense plan reduces each bucket, cut into one
+// segment per rank of the ring (the masters, for a hierarchical allreduce).
+static gf_status build_ring_tables(gf_plan *pl)
+{
+    pl->buckets.clear();
+    pl->ring_blocks.clear();
+    if (pl->chunk != 0) return GF_OK;
+    const int64_t A = gf_wire_granule(pl->wire);
+    for (size_t b = 0; b < pl->bucket_lo.size(); ++b) {
+        gf_bucket_dev bd;
+        bd.lo = pl->bucket_lo[b];
+        bd.hi = pl->bucket_hi[b];
+        bd.seg = gf_ring_segment_len(bd.hi - bd.lo, pl->ring_M, pl->wire);
+        pl->buckets.push_back(bd);
+        const int64_t Lb = bd.hi - bd.lo;
+        for (int32_t s = 0; s < pl->ring_M; ++s) {
+            const int64_t a = std::min<int64_t>(Lb, static_cast<int64_t>(s) * bd.seg);
+            const int64_t e = std::min<int64_t>(Lb, a + bd.seg);
+            const int64_t groups = (e - a + A - 1) / A;
+            const int64_t blocks = (groups + GF_RING_GROUPS_PER_BLOCK - 1) / GF_RING_GROUPS_PER_BLOCK;
+            for (int64_t i = 0; i < blocks; ++i) {
+                gf_ring_block rb;
+                rb.bucket = static_cast<int32_t>(b);
+                rb.segment = s;
+                rb.block_in_segment = static_cast<int32_t>(i);
+                rb.pad_ = 0;
+                pl->ring_blocks.push_back(rb);
+            }
+        }
+    }
+    if (pl->ring_blocks.size() > (size_t{1} << 30)) return GF_EINVAL;
+    return GF_OK;
 }
 
 static gf_status build_plan(gf_plan *pl, const int64_t *numel, int32_t m, int64_t theta,
@@ -79,35 +114,8 @@ static gf_status build_plan(gf_plan *pl, const int64_t *numel, int32_t m, int64_
     }
     for (int32_t t = 0; t < pl->n_tiles; ++t) pl->piece_start[t + 1] += pl->piece_start[t];
 
-    // Ring tables.  A CSC plan reduces the packed buffer as a single ring whose
-    // length is only known at call time; a dense plan reduces each bucket.
-    if (chunk == 0) {
-        const int64_t A = gf_wire_granule(wire);
-        for (size_t b = 0; b < pl->bucket_lo.size(); ++b) {
-            gf_bucket_dev bd;
-            bd.lo = pl->bucket_lo[b];
-            bd.hi = pl->bucket_hi[b];
-            bd.seg = gf_ring_segment_len(bd.hi - bd.lo, P, wire);
-            pl->buckets.push_back(bd);
-            const int64_t Lb = bd.hi - bd.lo;
-            for (int32_t s = 0; s < P; ++s) {
-                const int64_t a = std::min<int64_t>(Lb, static_cast<int64_t>(s) * bd.seg);
-                const int64_t e = std::min<int64_t>(Lb, a + bd.seg);
-                const int64_t groups = (e - a + A - 1) / A;
-                const int64_t blocks = (groups + GF_RING_GROUPS_PER_BLOCK - 1) / GF_RING_GROUPS_PER_BLOCK;
-                for (int64_t i = 0; i < blocks; ++i) {
-                    gf_ring_block rb;
-                    rb.bucket = static_cast<int32_t>(b);
-                    rb.segment = s;
-                    rb.block_in_segment = static_cast<int32_t>(i);
-                    rb.pad_ = 0;
-                    pl->ring_blocks.push_back(rb);
-                }
-            }
-        }
-        if (pl->ring_blocks.size() > (size_t{1} << 30)) return GF_EINVAL;
-    }
-    return GF_OK;
+    pl->ring_M = P;
+    return build_ring_tables(pl);
 }
 
 extern "C" gf_status gf_plan_create(gf_plan **out, const int64_t *tensor_numel, int32_t m,
@@ -199,7 +207,7 @@ extern "C" gf_status gf_plan_layout(const gf_plan *pl, int64_t *tensor_off, int6
 extern "C" int64_t gf_plan_ring_segment(const gf_plan *pl, int64_t L)
 {
     if (!pl || L < 0) return -1;
-    return gf_ring_segment_len(L, pl->P, pl->wire);
+    return gf_ring_segment_len(L, pl->ring_M, pl->wire);
 }
 
 extern "C" int32_t gf_plan_tiles(const gf_plan *pl) { return pl ? pl->n_tiles : -1; }
@@ -249,4 +257,21 @@ extern "C" gf_status gf_plan_set_grad_type(gf_plan *pl, gf_wire type)
     if (!pl || (type != GF_WIRE_F16 && type != GF_WIRE_F32)) return GF_EINVAL;
     pl->grad = type;
     return GF_OK;
+}
+
+// Section 2.4, hierarchical allreduce: M groups of P / M consecutive ranks, the
+// lowest rank of each group its master.  M = P (or 0) is the flat ring.
+extern "C" gf_status gf_plan_set_reduce_groups(gf_plan *pl, int32_t M)
+{
+    if (!pl || M < 0 || M > pl->P) return GF_EINVAL;
+    if (M == 0) M = pl->P;
+    if (pl->P % M != 0) return GF_EINVAL;
+    if (pl->on_device) return GF_ESTATE;       // the ring tables already went to the device
+    if (M == pl->ring_M) return GF_OK;
+    pl->ring_M = M;
+    try {
+        return build_ring_tables(pl);
+    } catch (const std::bad_alloc &) {
+        return GF_ENOMEM;
+    }
 }

@@ -8,6 +8,13 @@
 // 16 bytes from all P buffers starting at worker s, and writes the result once
 // (plus P copies when the all-gather outputs are requested).  A workgroup never
 // crosses a segment border, so s and the P base pointers are wave-uniform.
+//
+// Hierarchical allreduce (Section 2.4) is the same kernel with another visiting
+// order: the P ranks form M groups of G consecutive ranks, each group's values
+// are folded along the chain that ends on its lowest rank (the master),
+// y_g = x_{gG+1} + ... + x_{gG+G-1} + x_{gG}, and the M masters run the ring:
+// there are M segments, and segment s ends as y_s + y_{s+1} + ... + y_{s-1}.
+// G = 1 is the flat ring.
 #include "gf_device.h"
 
 namespace {
@@ -26,6 +33,7 @@ struct RingArgs {
     const int64_t *L_dev;
     int64_t L;
     int32_t P;
+    int32_t M, G;                     // ring participants (= segments) and ranks per group; M * G = P
     int32_t blocks_per_segment;       // CSC plans: workgroups per segment of a full bucket
     int64_t bucket_span;              // CSC plans: elements per full bucket of the packed buffer
 };
@@ -46,12 +54,34 @@ __device__ __forceinline__ gf_f32x4 hop16(gf_f32x4 a, gf_f32x4 b)
     return r;
 }
 
-template <typename W, bool DENSE>
+// Visiting order of the hierarchical fold: position pos = j * G + l stands for
+// rank ((s + j) mod M) * G + ((l + 1) mod G).  `feed` takes the values in that
+// order: the first of a group opens the group's partial sum, the last closes it
+// into the ring's running sum.
+struct HierWalk {
+    int G, M, g, l, j;
+    __device__ HierWalk(int s, int M_, int G_) : G(G_), M(M_), g(s), l(0), j(0) {}
+    __device__ int rank() const { return g * G + (l + 1 == G ? 0 : l + 1); }
+    __device__ void next()
+    {
+        if (++l == G) { l = 0; ++j; g = g + 1 == M ? 0 : g + 1; }
+    }
+};
+
+template <typename T, typename Add>
+__device__ __forceinline__ void hier_feed(T &v, T &y, const T &x, int l, int j, int G, Add add)
+{
+    y = l == 0 ? x : add(y, x);
+    if (l + 1 == G) v = j == 0 ? y : add(v, y);
+}
+
+template <typename W, bool DENSE, bool HIER>
 __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArgs a)
 {
     using V = typename vec16<W>::type;
     constexpr int A = vec16<W>::n;
     const int P = a.P;
+    const int M = HIER ? a.M : P;     // segments per bucket
     int64_t lo, hi, seg;
     int s, bis;
     if constexpr (DENSE) {
@@ -66,13 +96,13 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
         // buckets are [b * span, min(L, (b + 1) * span)).
         int64_t L = a.L;
         if (a.L_dev) { const int64_t d = *a.L_dev; L = d < 0 ? 0 : (d < L ? d : L); }
-        const int per_bucket = P * a.blocks_per_segment;
+        const int per_bucket = M * a.blocks_per_segment;
         const int b = blockIdx.x / per_bucket;
         const int r = blockIdx.x - b * per_bucket;
         lo = static_cast<int64_t>(b) * a.bucket_span;
         if (lo >= L) return;
         hi = lo + a.bucket_span < L ? lo + a.bucket_span : L;
-        const int64_t per = (hi - lo + P - 1) / P;
+        const int64_t per = (hi - lo + M - 1) / M;
         seg = (per + A - 1) / A * A;
         s = r / a.blocks_per_segment;
         bis = r - s * a.blocks_per_segment;
@@ -106,23 +136,45 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
             const __amdgpu_buffer_rsrc_t r = gf_make_buf(gf_global(static_cast<const W *>(a.send[q])) + blk, bytes);
             return __builtin_bit_cast(V, gf_buf_ld128u<AUX>(r, off));
         };
-        int q = s;
-        V v = ld(q);
-        int j = 1;
         constexpr int U = 8;
-        for (; j + U - 1 < P; j += U) {
-            V x[U];
+        V v;
+        if constexpr (HIER) {
+            const int G = a.G;
+            auto add = [](const V &p, const V &q) { return hop16(p, q); };
+            HierWalk rd(s, M, G), ap(s, M, G);       // one walks ahead issuing loads, one applies them
+            V y = {};
+            v = y;
+            int pos = 0;
+            for (; pos + U <= P; pos += U) {
+                V x[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                q = q + 1 == P ? 0 : q + 1;
-                x[u] = ld(q);
+                for (int u = 0; u < U; ++u) { x[u] = ld(rd.rank()); rd.next(); }
+#pragma unroll
+                for (int u = 0; u < U; ++u) { hier_feed(v, y, x[u], ap.l, ap.j, G, add); ap.next(); }
             }
+            for (; pos < P; ++pos) {
+                const V x = ld(ap.rank());
+                hier_feed(v, y, x, ap.l, ap.j, G, add);
+                ap.next();
+            }
+        } else {
+            int q = s;
+            v = ld(q);
+            int j = 1;
+            for (; j + U - 1 < P; j += U) {
+                V x[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v = hop16(v, x[u]);
-        }
-        for (; j < P; ++j) {
-            q = q + 1 == P ? 0 : q + 1;
-            v = hop16(v, ld(q));
+                for (int u = 0; u < U; ++u) {
+                    q = q + 1 == P ? 0 : q + 1;
+                    x[u] = ld(q);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) v = hop16(v, x[u]);
+            }
+            for (; j < P; ++j) {
+                q = q + 1 == P ? 0 : q + 1;
+                v = hop16(v, ld(q));
+            }
         }
         gf_buf_st<GF_AUX_CACHED>(__builtin_bit_cast(gf_u32x4, v),
                                  gf_make_buf(gf_global(static_cast<W *>(a.reduced)) + blk, bytes), off);
@@ -132,11 +184,23 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
                                          gf_make_buf(gf_global(static_cast<W *>(a.allgather[r])) + blk, bytes), off);
     } else {
         for (int i = 0; i < n; ++i) {
-            int q = s;
-            W v = static_cast<const W *>(a.send[q])[e + i];
-            for (int j = 1; j < P; ++j) {
-                q = q + 1 == P ? 0 : q + 1;
-                v = gf_hop_add(v, static_cast<const W *>(a.send[q])[e + i]);
+            W v;
+            if constexpr (HIER) {
+                auto add = [](W p, W q) { return gf_hop_add(p, q); };
+                HierWalk ap(s, M, a.G);
+                W y = 0;
+                v = 0;
+                for (int pos = 0; pos < P; ++pos) {
+                    hier_feed(v, y, static_cast<const W *>(a.send[ap.rank()])[e + i], ap.l, ap.j, a.G, add);
+                    ap.next();
+                }
+            } else {
+                int q = s;
+                v = static_cast<const W *>(a.send[q])[e + i];
+                for (int j = 1; j < P; ++j) {
+                    q = q + 1 == P ? 0 : q + 1;
+                    v = gf_hop_add(v, static_cast<const W *>(a.send[q])[e + i]);
+                }
             }
             static_cast<W *>(a.reduced)[e + i] = v;
             if (a.allgather)
@@ -166,32 +230,38 @@ extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *se
     a.L = L;
     a.L_dev = L_dev;
     a.P = pl->P;
+    a.M = pl->ring_M;
+    a.G = pl->P / pl->ring_M;
+    const bool hier = a.G > 1;
+    const bool f16 = pl->wire == GF_WIRE_F16;
+    const dim3 block(GF_RING_GROUPS_PER_BLOCK);
     if (dense) {
         a.buckets = pl->d_buckets;
         a.blocks = pl->d_ring_blocks;
         const size_t nb = pl->ring_blocks.size();
         if (nb == 0) return GF_OK;
-        if (pl->wire == GF_WIRE_F16)
-            hipLaunchKernelGGL((k_ring<uint16_t, true>), dim3(static_cast<unsigned>(nb)), dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
-        else
-            hipLaunchKernelGGL((k_ring<float, true>), dim3(static_cast<unsigned>(nb)), dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
+        const dim3 grid(static_cast<unsigned>(nb));
+        if (f16 && !hier) hipLaunchKernelGGL((k_ring<uint16_t, true, false>), grid, block, 0, st, a);
+        else if (f16) hipLaunchKernelGGL((k_ring<uint16_t, true, true>), grid, block, 0, st, a);
+        else if (!hier) hipLaunchKernelGGL((k_ring<float, true, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((k_ring<float, true, true>), grid, block, 0, st, a);
     } else {
         if (L == 0) return GF_OK;
         const int64_t A = gf_wire_granule(pl->wire);
         const int64_t span = gf_csc_bucket_span(pl);
         const int64_t full = span < L ? span : L;                      // longest bucket (upper bound with L_dev)
         const int64_t n_buckets = (L + span - 1) / span;
-        const int64_t seg = gf_ring_segment_len(full, pl->P, pl->wire);
+        const int64_t seg = gf_ring_segment_len(full, pl->ring_M, pl->wire);
         const int64_t groups = seg / A;
         const int64_t bps = (groups + GF_RING_GROUPS_PER_BLOCK - 1) / GF_RING_GROUPS_PER_BLOCK;
-        if (bps * pl->P * n_buckets > (int64_t{1} << 30)) return GF_EINVAL;
+        if (bps * pl->ring_M * n_buckets > (int64_t{1} << 30)) return GF_EINVAL;
         a.blocks_per_segment = static_cast<int32_t>(bps);
         a.bucket_span = span;
-        const dim3 grid(static_cast<unsigned>(bps * pl->P * n_buckets));
-        if (pl->wire == GF_WIRE_F16)
-            hipLaunchKernelGGL((k_ring<uint16_t, false>), grid, dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
-        else
-            hipLaunchKernelGGL((k_ring<float, false>), grid, dim3(GF_RING_GROUPS_PER_BLOCK), 0, st, a);
+        const dim3 grid(static_cast<unsigned>(bps * pl->ring_M * n_buckets));
+        if (f16 && !hier) hipLaunchKernelGGL((k_ring<uint16_t, false, false>), grid, block, 0, st, a);
+        else if (f16) hipLaunchKernelGGL((k_ring<uint16_t, false, true>), grid, block, 0, st, a);
+        else if (!hier) hipLaunchKernelGGL((k_ring<float, false, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((k_ring<float, false, true>), grid, block, 0, st, a);
     }
     GF_LAUNCH_CHECK();
     return GF_OK;

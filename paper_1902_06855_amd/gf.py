@@ -32,7 +32,8 @@ GF_WIRE_F16, GF_WIRE_F32 = 0, 1
 GF_PHASE_ACCUM, GF_PHASE_PACK = 1, 2
 
 EXPORTS = (
-    "gf_status_string", "gf_plan_create", "gf_plan_set_grad_type", "gf_plan_to_device", "gf_plan_destroy", "gf_plan_info",
+    "gf_status_string", "gf_plan_create", "gf_plan_set_grad_type", "gf_plan_set_reduce_groups",
+    "gf_plan_to_device", "gf_plan_destroy", "gf_plan_info",
     "gf_plan_layout", "gf_plan_ring_segment", "gf_plan_tiles", "gf_plan_tile_pieces",
     "gf_plan_workspace_bytes", "gf_plan_warmup_k", "gf_fuse_pack", "gf_chunk_score_select", "gf_ring_reduce_sim",
     "gf_unpack_apply", "gf_unpack_sgd_update",
@@ -52,6 +53,7 @@ _status_string = _sig("gf_status_string", C.c_char_p, C.c_int)
 _plan_create = _sig("gf_plan_create", C.c_int, C.POINTER(_vp), C.POINTER(_i64), _i32, _i64, _i32, _i32, C.c_int)
 _plan_to_device = _sig("gf_plan_to_device", C.c_int, _vp)
 _plan_set_grad_type = _sig("gf_plan_set_grad_type", C.c_int, _vp, C.c_int)
+_plan_set_reduce_groups = _sig("gf_plan_set_reduce_groups", C.c_int, _vp, _i32)
 _plan_destroy = _sig("gf_plan_destroy", None, _vp)
 _plan_info = _sig("gf_plan_info", C.c_int, _vp, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_i32))
 _plan_layout = _sig("gf_plan_layout", C.c_int, _vp, C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64))
@@ -113,7 +115,7 @@ class Plan:
     """Owner of a gf_plan handle."""
 
     def __init__(self, tensor_numel: Sequence[int], theta_elems: int, chunk_elems: int, P: int,
-                 wire: int = GF_WIRE_F16, to_device: bool = True):
+                 wire: int = GF_WIRE_F16, to_device: bool = True, groups: int = 0):
         m = len(tensor_numel)
         arr = (_i64 * m)(*[int(s) for s in tensor_numel])
         h = _vp()
@@ -125,6 +127,8 @@ class Plan:
         _check(_plan_info(h, C.byref(N), C.byref(nc), C.byref(nb)), "gf_plan_info")
         self.N, self.n_chunks, self.n_buckets = N.value, nc.value, nb.value
         self._workspace = None
+        if groups:
+            self.set_reduce_groups(groups)
         if to_device:
             self.to_device()
 
@@ -134,6 +138,10 @@ class Plan:
     def set_grad_type(self, wire: int) -> None:
         """GF_WIRE_F16: the gradients given to gf_fuse_pack are fp16; GF_WIRE_F32 (default): fp32."""
         _check(_plan_set_grad_type(self.handle, int(wire)), "gf_plan_set_grad_type")
+
+    def set_reduce_groups(self, M: int) -> None:
+        """Hierarchical allreduce with M groups (0 or P: the flat ring); before to_device only."""
+        _check(_plan_set_reduce_groups(self.handle, int(M)), "gf_plan_set_reduce_groups")
 
     def layout(self) -> Tuple[List[int], List[int], List[int]]:
         off = (_i64 * self.m)()

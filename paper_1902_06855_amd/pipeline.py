@@ -31,7 +31,7 @@ class Pipeline:
                  k: int = 0, mu: float = 1.0, wire: str = "f16", schedule: str = "lagged",
                  scatter_out: bool = False, allgather: bool = False, device: str = "cuda",
                  sgd: Optional[tuple] = None, k_max: Optional[int] = None, grad: str = "f32",
-                 zero_copy: bool = False):
+                 zero_copy: bool = False, groups: int = 0):
         assert schedule in ("lagged", "immediate")
         if zero_copy and not (chunk == 0 and grad == "f16" and wire == "f16"):
             raise ValueError("zero_copy needs a dense plan with fp16 pools on an fp16 wire")
@@ -41,7 +41,8 @@ class Pipeline:
         self.alpha = float(np.float32(1.0) / np.float32(loss_scale))   # 1/S rounded once to fp32
         self.wire = gf.GF_WIRE_F16 if wire == "f16" else gf.GF_WIRE_F32
         self.wdtype = torch.float16 if wire == "f16" else torch.float32
-        self.plan = gf.Plan(self.sizes, min(int(theta), 1 << 60), self.chunk, self.P, self.wire)
+        # groups: hierarchical allreduce with that many groups (Section 2.4); 0 = flat ring
+        self.plan = gf.Plan(self.sizes, min(int(theta), 1 << 60), self.chunk, self.P, self.wire, groups=groups)
         if grad == "f16":                      # gradients arrive as fp16 (mixed-precision backward)
             self.plan.set_grad_type(gf.GF_WIRE_F16)
         self.N, self.n_chunks, self.m = self.plan.N, self.plan.n_chunks, len(self.sizes)

@@ -124,6 +124,18 @@ def config(name: str) -> Workload:
         if name == net + "_fp16pool":          # fp16 gradients already in the pool, reduced in place
             return Workload(name, sizes(), P=8, chunk=0, density=1.0, loss_scale=S, theta=32 * MB // 2,
                             grad="f16", extra={"zero_copy": True})
+    if name == "alexnet_csc_hier":             # 16 ranks in 4 groups: the example of Section 2.4's figure
+        w = config("alexnet_csc")
+        w.name, w.extra = name, {"groups": 4}
+        return w
+    if name == "resnet50_csc_hier":            # 64 ranks in 8 groups of 8
+        w = config("resnet50_csc")
+        w.name, w.extra = name, {"groups": 8}
+        return w
+    if name == "alexnet_dense_hier":           # 8 ranks in 2 groups
+        w = config("alexnet_dense")
+        w.name, w.extra = name, {"groups": 2}
+        return w
     if name == "alexnet_csc_fp16in":           # sparse path fed with fp16 gradients
         w = config("alexnet_csc")
         w.name, w.grad = name, "f16"
@@ -132,7 +144,8 @@ def config(name: str) -> Workload:
 
 
 LADDER_NAMES = ("alexnet_pertensor_fp32", "alexnet_pertensor_fp16", "alexnet_fp16pool", "alexnet_csc_fp16in",
-                "resnet50_pertensor_fp32", "resnet50_pertensor_fp16", "resnet50_fp16pool")
+                "resnet50_pertensor_fp32", "resnet50_pertensor_fp16", "resnet50_fp16pool",
+                "alexnet_dense_hier", "alexnet_csc_hier", "resnet50_csc_hier")
 
 CONFIG_NAMES = ("tiny", "alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb",
                 "alexnet_csc", "resnet50_csc")

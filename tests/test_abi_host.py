@@ -76,6 +76,19 @@ def test_ring_segment_fp32_wire():
     assert plan.ring_segment(-1) == -1
 
 
+def test_reduce_groups_change_the_ring_size_and_reject_bad_counts():
+    plan = gf.Plan([100, 200], 1 << 40, 0, 12, to_device=False)
+    for M in (1, 2, 3, 4, 6, 12, 0):
+        plan.set_reduce_groups(M)
+        for L in (0, 1, 5, 24, 25, 300):
+            assert plan.ring_segment(L) == ob.ring_segment(L, M or 12, "f16")
+    for M in (5, 7, 13, -1, 24):
+        with pytest.raises(gf.GfError) as e:
+            plan.set_reduce_groups(M)
+        assert e.value.status == gf.GF_EINVAL
+    assert plan.ring_segment(300) == ob.ring_segment(300, 12, "f16")       # a refused count changes nothing
+
+
 @pytest.mark.parametrize("sizes,chunk", [([7, 1, 64, 333, 2, 1024, 5], 96), ([50, 8, 700, 33, 1200, 64, 5], 0),
                                          (wl.resnet50_sizes(), 8192), ([5], 3), ([3, 3, 3], 3)])
 def test_tile_pieces_tile_the_pool_in_generation_order(sizes, chunk):

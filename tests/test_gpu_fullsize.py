@@ -55,14 +55,32 @@ def fold_in_ring_order(cols: np.ndarray, seg_index: np.ndarray) -> np.ndarray:
     return out
 
 
+def fold_in_hierarchical_order(cols: np.ndarray, seg_index: np.ndarray, M: int) -> np.ndarray:
+    """Hierarchical allreduce with M groups of consecutive workers (Section 2.4), one rounded half
+    addition at a time: each group's chain runs from the rank after its master round to the
+    master, then the masters' ring starts at the group that owns the element's segment."""
+    P, n = cols.shape
+    G = P // M
+    add = lambda a, b: ob.ring_fold(np.stack([a, b]), "f16")
+    y = []
+    for g in range(M):
+        v = cols[g * G + 1 % G].copy()
+        for q in range(2, G + 1):
+            v = add(v, cols[g * G + q % G])
+        y.append(v)
+    return fold_in_ring_order(np.stack(y), seg_index)
+
+
 # ------------------------------------------------------------------- dense
 
-@pytest.mark.parametrize("name", ["alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb"])
-def test_dense_full_size_sampled(mods, name):
+@pytest.mark.parametrize("name,groups", [("alexnet_dense", 0), ("resnet50_dense_4mb", 0), ("resnet50_dense_64mb", 0),
+                                         ("alexnet_dense", 2), ("resnet50_dense_4mb", 4)])
+def test_dense_full_size_sampled(mods, name, groups):
     gf, pl = mods
     w = wl.config(name)
+    M = groups or w.P                                 # ranks in the ring: all, or the group masters
     grads = wl.gradients(w, 0, device="cuda")
-    pipe = pl.Pipeline(w.sizes, w.P, 0, w.theta, w.loss_scale)
+    pipe = pl.Pipeline(w.sizes, w.P, 0, w.theta, w.loss_scale, groups=groups)
     pipe.set_gradients(grads)
     pipe.out_pool.fill_(-9.0)
     pipe.step()
@@ -73,9 +91,9 @@ def test_dense_full_size_sampled(mods, name):
     rng = np.random.default_rng(7)
     idx = [np.arange(0, 4096), np.arange(w.N - 4096, w.N)]
     for a, b in zip(lo, hi):                          # both ends of every bucket and of its segments
-        seg = ob.ring_segment(b - a, w.P)
+        seg = ob.ring_segment(b - a, M)
         idx += [np.arange(a, min(b, a + 64)), np.arange(max(a, b - 64), b)]
-        for s in range(1, w.P):
+        for s in range(1, M):
             e = a + s * seg
             if e < b:
                 idx.append(np.arange(max(a, e - 16), min(b, e + 16)))
@@ -94,8 +112,8 @@ def test_dense_full_size_sampled(mods, name):
     seg_index = np.empty(idx.size, dtype=np.int64)
     for b in np.unique(b_of):
         m = b_of == b
-        seg_index[m] = (idx[m] - lo[b]) // ob.ring_segment(hi[b] - lo[b], w.P)
-    reduced = fold_in_ring_order(send, seg_index)
+        seg_index[m] = (idx[m] - lo[b]) // ob.ring_segment(hi[b] - lo[b], M)
+    reduced = fold_in_hierarchical_order(send, seg_index, M) if groups else fold_in_ring_order(send, seg_index)
     assert np.array_equal(u16(pipe.reduced[tidx].cpu().numpy()), reduced), "reduced"
     out = ob.unpack_dense(reduced, np.float32(1.0) / np.float32(w.loss_scale))
     assert np.array_equal(u32(pipe.out_pool[tidx].cpu().numpy()), u32(out)), "out"

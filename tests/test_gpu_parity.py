@@ -639,3 +639,95 @@ def test_fp16_pools_reduced_in_place(gfm, theta):
         assert torch.equal(dev[p].cpu().view(torch.int16), pools[p].view(torch.int16))
     with pytest.raises(ValueError):
         pl.Pipeline(w.sizes, w.P, 0, theta, w.loss_scale, grad="f32", zero_copy=True)
+
+
+# ------------------------------------------------- hierarchical allreduce order (Section 2.4)
+
+@pytest.mark.parametrize("P,M,L", [(4, 2, 4096), (16, 4, 100003), (8, 1, 70000), (64, 8, 262144), (6, 3, 1000),
+                                   (12, 2, 7), (64, 16, 33333), (9, 3, 8), (20, 4, 50001)])
+def test_hierarchical_order_single_bucket_bit_exact(gfm, P, M, L):
+    gf, _ = gfm
+    rng = np.random.default_rng(P * 7 + M + L)
+    C = 1024
+    nch = -(-L // C)
+    plan = gf.Plan([nch * C], 1 << 40, C, P, groups=M)
+    assert plan.ring_segment(L) == ob.ring_segment(L, M)
+    x = _halves(rng, P, L)
+    want = ob.hier_fold(x, M, "f16")
+    send = [torch.from_numpy(x[p].view(np.float16)).cuda() for p in range(P)]
+    red = torch.zeros(L, dtype=torch.float16, device="cuda")
+    ag = [torch.zeros(L, dtype=torch.float16, device="cuda") for _ in range(P)]
+    L_dev = torch.tensor([L], dtype=torch.int64, device="cuda")
+    gf.gf_ring_reduce_sim(plan, gf.ptr_table(send), L, red, L_dev=L_dev, allgather_out=gf.ptr_table(ag))
+    torch.cuda.synchronize()
+    same_bits(red.view(torch.int16), want.view(np.int16), f"hier P={P} M={M} L={L}")
+    for r in (0, P - 1):                     # the broadcast leaves every rank with the same buffer
+        same_bits(ag[r].view(torch.int16), want.view(np.int16), f"broadcast rank {r}")
+
+
+def test_hierarchical_order_unaligned_and_fp32_wire(gfm):
+    gf, _ = gfm
+    rng = np.random.default_rng(4)
+    P, M, L = 6, 2, 5001
+    plan = gf.Plan([8192], 1 << 40, 8192, P, groups=M)
+    x = _halves(rng, P, L)
+    want = ob.hier_fold(x, M, "f16")
+    raw = [torch.zeros(L + 8, dtype=torch.float16, device="cuda") for _ in range(P)]
+    send = [raw[p][1 + p % 2:1 + p % 2 + L] for p in range(P)]       # 2-byte aligned only: scalar path
+    for p in range(P):
+        send[p].copy_(torch.from_numpy(x[p].view(np.float16)))
+    red = torch.zeros(L, dtype=torch.float16, device="cuda")
+    gf.gf_ring_reduce_sim(plan, gf.ptr_table(send), L, red)
+    torch.cuda.synchronize()
+    same_bits(red.view(torch.int16), want.view(np.int16), "unaligned hierarchical")
+
+    plan32 = gf.Plan([8192], 1 << 40, 8192, P, wire=gf.GF_WIRE_F32, groups=M)
+    y = (rng.standard_normal((P, L)) * 10.0 ** rng.integers(-6, 6, size=(P, 1))).astype(np.float32)
+    want32 = ob.hier_fold(y, M, "f32")
+    red32 = torch.zeros(L, dtype=torch.float32, device="cuda")
+    gf.gf_ring_reduce_sim(plan32, gf.ptr_table([torch.from_numpy(y[p]).cuda() for p in range(P)]), L, red32)
+    torch.cuda.synchronize()
+    same_bits(red32, want32, "fp32 hierarchical")
+
+
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+def test_hierarchical_order_dense_buckets(gfm, wire):
+    gf, pl = gfm
+    w = odd_workload(P=6, chunk=0, wire=wire)
+    for M, theta in ((2, 1000), (3, 0), (1, 1 << 40), (6, 64)):
+        grads = cpu_grads(w, 0)
+        pools = pools_np(grads, w.sizes)
+        ref = op.dense_iteration(pools, w.sizes, theta, w.loss_scale, wire, groups=M)
+        pipe = pl.Pipeline(w.sizes, w.P, 0, theta, w.loss_scale, wire=wire, groups=M)
+        pipe.set_gradients(to_dev(grads))
+        pipe.step()
+        torch.cuda.synchronize()
+        it, nt = (torch.int16, np.int16) if wire == "f16" else (torch.int32, np.int32)
+        same_bits(pipe.reduced.view(it), ref["reduced"].view(nt), f"reduced M={M} theta={theta}")
+        same_bits(pipe.out_pool, ref["out"], f"out M={M}")
+
+
+@pytest.mark.parametrize("schedule", ["lagged", "immediate"])
+def test_hierarchical_order_csc_iterations(gfm, schedule):
+    """Several sparse iterations with the packed buffer reduced hierarchically, bucket-wise."""
+    gf, pl = gfm
+    for w, M, theta in ((odd_workload(P=4, chunk=96), 2, 1 << 40), (wl.scaled(wl.config("tiny"), 4), 2, 3000),
+                        (odd_workload(P=6, chunk=64, density=0.5), 3, 200)):
+        nc = ob.n_chunks(w.N, w.chunk)
+        k = w.k_for(nc)
+        pipe = pl.Pipeline(w.sizes, w.P, w.chunk, theta, w.loss_scale, k=k, schedule=schedule, groups=M)
+        st = op.new_state(w.P, w.N)
+        for t in range(3):
+            grads = cpu_grads(w, t)
+            pipe.set_gradients(to_dev(grads))
+            pipe.out_pool.fill_(-4.0)
+            pipe.step()
+            torch.cuda.synchronize()
+            out = np.full(w.N, np.float32(-4.0))
+            r = op.csc_iteration(st, pools_np(grads, w.sizes), w.chunk, k, w.loss_scale, w.mu, schedule,
+                                 out=out, theta=theta, groups=M)
+            L = r["send"].shape[1]
+            same_bits(pipe.reduced[:L].view(torch.int16), r["reduced"].view(np.int16), f"t={t} reduced")
+            same_bits(pipe.out_pool, out, f"t={t} out")
+            nxt = r["sel_next"] if schedule == "lagged" else r["sel"]
+            assert np.array_equal(pipe.sel.cpu().numpy(), nxt), f"t={t} selection"
