@@ -176,7 +176,11 @@ int32_t gf_plan_warmup_k(const gf_plan *plan, double final_density, int64_t iter
  *                        send = wire(acc * S), hg <- +0.  Others: hg <- mu*acc.
  * phase = ACCUM | PACK   both in a single pass over the data (sel_idx is
  *                        already known: the paper's schedule, or the dense path).
- * mu is Algorithm 1's "momentum" applied to the historical gradient. */
+ * mu is Algorithm 1's "momentum" applied to the historical gradient.
+ * workspace (gf_plan_workspace_bytes, 256-byte aligned) is needed when sel_idx
+ * is given together with GF_PHASE_PACK, and when chunk_l1 is asked for on a plan
+ * whose chunks are longer than 8192 elements (partial norms are combined
+ * there); GF_EINVAL if it is missing then.  It may be NULL otherwise. */
 gf_status gf_fuse_pack(const gf_plan *plan, uint32_t phase,
                        const void *const *grads, const float *const *pools,
                        float *const *residual,

@@ -3,13 +3,20 @@
 // momentum * g), per-chunk L1 norms (Section 3.2) and the fp32 -> wire cast
 // with loss scaling (Section 2.5), as one HBM-streaming pass per worker tile.
 //
-// One workgroup handles one (worker, tile) pair; a tile is a chunk of a CSC
-// plan or a fixed slice of the pool of a dense plan.  Whether the tile is sent
-// is uniform across the workgroup, so each case runs its own straight-line
-// inner loop of 128-bit loads and stores with several loads in flight.  With
-// scattered per-tensor gradients a tile may be made of pieces of several
-// tensors; their addresses are put in a small LDS table so that the tile is
-// still swept as one run.
+// A tile is a chunk of a CSC plan or a fixed slice of the pool of a dense plan;
+// tiles longer than GF_FUSE_SUB elements are cut into sub-tiles of that length.
+// One workgroup handles one (worker, tile, sub-tile) triple.  Whether the tile
+// is sent is uniform across the workgroup, so each case runs its own
+// straight-line inner loop of 128-bit loads and stores with several loads in
+// flight.  With scattered per-tensor gradients a tile may be made of pieces of
+// several tensors; their addresses are put in a small LDS table so that the
+// sub-tile is still swept as one run.
+//
+// Workgroups are dealt to the eight XCDs round-robin by the hardware, and each
+// XCD has its own L2.  The work list is therefore permuted so that a run of
+// consecutive sub-tiles (a few hundred KB of one worker's pool) is handled by
+// one XCD: consecutive 32 KB sub-tiles spread over all XCDs use only part of
+// each L2's channels and stream measurably slower.
 #include <type_traits>
 
 #include "gf_device.h"
@@ -38,10 +45,32 @@ struct FuseArgs {
     float *chunk_l1;
     const int32_t *piece_start;
     const gf_piece *pieces;
+    const gf_unit_src *unit_src; // [n_tiles * subs]
+    double *l1_part;             // [P * n_tiles * subs] partial norms when subs > 1
     int64_t N;
-    int32_t tile, n_tiles, units; // units: work items per worker
+    int32_t tile, n_tiles, units; // units: tiles to visit per worker
+    int32_t sub, subs;            // sub-tile length (elements) and sub-tiles per tile
+    uint32_t total;               // workgroups = P * units * subs
+    int32_t grp_shift;            // log2 of the consecutive work items one XCD takes
     float S, mu;
 };
+
+constexpr int N_XCD = 8;
+
+// 1: issue the first batch of historical-gradient loads before the gradients' address is known
+#ifndef GF_FUSE_PREFETCH
+#define GF_FUSE_PREFETCH 1
+#endif
+
+// Work item of a workgroup: the hardware hands workgroup b to XCD b mod 8, so item
+// numbers are dealt in runs of 2^grp_shift per XCD.  A permutation of [0, total).
+__device__ __forceinline__ uint32_t xcd_order(uint32_t b, uint32_t total, int grp_shift)
+{
+    const uint32_t span = static_cast<uint32_t>(N_XCD) << grp_shift;
+    if (b >= total / span * span) return b;                 // ragged end: identity
+    const uint32_t x = b % N_XCD, i = b / N_XCD;
+    return ((i >> grp_shift) * span) + (x << grp_shift) + (i & ((1u << grp_shift) - 1u));
+}
 
 template <int F, typename W>
 __device__ __forceinline__ void elem4(const gf_f32x4 g, const gf_f32x4 r, gf_f32x4 &res_out,
@@ -86,35 +115,55 @@ struct GradSrc {
     }
 };
 
-// One tile (or one contiguous piece of it) of `len` elements.  res / snd are
-// already offset to its first element; unused pointers are null.  Gradients
-// and the historical gradient are touched exactly once per iteration, so they
-// go around the caches (nontemporal); the send buffer is read back by the ring
-// kernel right away and stays cacheable.
-template <int F, typename W, typename GT, int NT, int U>
-__device__ __forceinline__ void run(const GradSrc<GT> &src, float *res_, W *snd_, int len, bool vec,
-                                    float S, float mu, double &l1)
+// One run of `len` elements.  res / snd are already offset to its first element;
+// unused pointers are null.  Gradients and the historical gradient are touched
+// exactly once per iteration, so they go around the caches (nontemporal); the
+// send buffer is read back by the ring kernel right away and stays cacheable.
+//
+// Where the gradients live is found by `resolve(src)`, which returns 1 (source
+// known, 128-bit path allowed), 0 (source known, element-wise only) or -1 (not
+// a single source: nothing is done and false is returned).  With scattered
+// tensors that takes a chain of dependent table look-ups, so the first batch of
+// historical-gradient loads, whose address is known at once, is issued before it.
+template <int F, typename W, typename GT, int NT, int U, typename Resolve>
+__device__ __forceinline__ bool run(Resolve &&resolve, float *res_, W *snd_, int len, float S, float mu, double &l1)
 {
     using G4 = typename gf_wire4<GT>::type;                // four gradients as stored
     GF_GLOBAL float *__restrict__ res = gf_global(res_);
     GF_GLOBAL W *__restrict__ snd = gf_global(snd_);
     using W4 = typename gf_wire4<W>::type;
     constexpr bool WRITES_RES = (F & (F_KEEP | F_ZERO)) != 0;
+    bool vec = true;
     if constexpr ((F & F_RES) || WRITES_RES) vec = vec && gf_aligned(res, 16);
     if constexpr (F & F_SEND) vec = vec && gf_aligned(snd, sizeof(W4));
+    const uint32_t run_bytes = static_cast<uint32_t>(len) * 4u;
+    const __amdgpu_buffer_rsrc_t rb = gf_make_buf(res, ((F & F_RES) || WRITES_RES) ? run_bytes : 0u);
+
+    constexpr bool PREFETCH = GF_FUSE_PREFETCH && (F & F_RES) && (F & F_G);
+    gf_f32x4 pre[U] = {};
+    bool have_pre = PREFETCH && vec && U * NT <= (len >> 2);     // uniform: a whole first batch exists
+    if constexpr (PREFETCH) {
+        if (have_pre) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) pre[u] = gf_buf_ld128<GF_AUX_STREAM>(rb, (threadIdx.x + u * NT) * 16);
+        }
+    }
+
+    GradSrc<GT> src{nullptr, nullptr, nullptr, 0};
+    const int how = resolve(src);
+    if (how < 0) return false;
+    vec = vec && how > 0;
     const int nvec = vec ? (len >> 2) : 0;
     auto g4 = [&](int v) { return reinterpret_cast<const GF_GLOBAL G4 *>(gf_global(src.at(v << 2))); };
     auto widen = [](G4 x) { float a, b, c, d; gf_unpack4(x, a, b, c, d); return gf_pack4(a, b, c, d); };
 
     // 128-bit sweep.  A direct source goes through buffer descriptors (one per stream, made
-    // for exactly this run); a tile pieced together from several tensors reads its gradients
+    // for exactly this run); a run pieced together from several tensors reads its gradients
     // through per-lane global addresses instead.
     constexpr int WB = static_cast<int>(sizeof(W4));      // bytes of four wire elements
-    const uint32_t run_bytes = static_cast<uint32_t>(len) * 4u;
     constexpr int GB = static_cast<int>(sizeof(G4));      // bytes of four gradients
     const __amdgpu_buffer_rsrc_t gb = gf_make_buf(gf_global(src.base), (F & F_G) && src.n == 0
                                                   ? static_cast<uint32_t>(len) * sizeof(GT) : 0u);
-    const __amdgpu_buffer_rsrc_t rb = gf_make_buf(res, ((F & F_RES) || WRITES_RES) ? run_bytes : 0u);
     const __amdgpu_buffer_rsrc_t sb = gf_make_buf(snd, (F & F_SEND) ? static_cast<uint32_t>(len) * sizeof(W) : 0u);
     auto sweep = [&](auto direct_tag) {
         constexpr bool DIRECT = decltype(direct_tag)::value;
@@ -129,10 +178,19 @@ __device__ __forceinline__ void run(const GradSrc<GT> &src, float *res_, W *snd_
         int v = threadIdx.x;
         for (; v + (U - 1) * NT < nvec; v += U * NT) {
             gf_f32x4 gg[U], rr[U];
+            if (have_pre) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if constexpr (F & F_G) gg[u] = load_g(v + u * NT);
-                if constexpr (F & F_RES) rr[u] = gf_buf_ld128<GF_AUX_STREAM>(rb, (v + u * NT) * 16);
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (F & F_G) gg[u] = load_g(v + u * NT);
+                    rr[u] = pre[u];
+                }
+                have_pre = false;
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (F & F_G) gg[u] = load_g(v + u * NT);
+                    if constexpr (F & F_RES) rr[u] = gf_buf_ld128<GF_AUX_STREAM>(rb, (v + u * NT) * 16);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -163,97 +221,163 @@ __device__ __forceinline__ void run(const GradSrc<GT> &src, float *res_, W *snd_
         if constexpr (F & F_KEEP) res[i] = mu * a;
         if constexpr (F & F_ZERO) res[i] = 0.f;
     }
+    return true;
 }
 
-constexpr int MAX_FLAT_PIECES = 64;   // more pieces than this in one tile are walked one by one
+constexpr int MAX_FLAT_PIECES = 64;   // more pieces than this in one run are walked one by one
 
+// What a workgroup needs from the tables, fetched in one go at its start (every
+// address here depends on the kernel arguments and the work item only).
+template <typename GT>
+struct Fetched {
+    float *res_p;            // residual[p]
+    void *snd_p;             // sendbuf[p]
+    const GT *pool_p;        // tab[p * tab_stride]: the worker's pool, or its first tensor
+    gf_unit_src us;          // single-tensor source of this sub-tile, if any
+};
+
+// Elements [lo, lo + len) of tile `tile` of worker p (lo a multiple of 4, the range inside the tile).
 template <int F, typename W, typename GT, int NT, int U>
-__device__ __forceinline__ void tile_body(const FuseArgs &a, int p, int tile, int64_t slot, double &l1)
+__device__ __forceinline__ void tile_body(const FuseArgs &a, const Fetched<GT> &f, int p, int tile, int64_t slot,
+                                          int lo, int len, double &l1)
 {
     constexpr unsigned GALIGN = 4 * sizeof(GT);            // alignment the vector path needs
+    if (len <= 0) return;                                  // sub-tile past the end of a short last tile
     const int64_t tile_lo = static_cast<int64_t>(tile) * a.tile;
-    const int64_t left = a.N - tile_lo;
-    const int tile_len = left < a.tile ? static_cast<int>(left) : a.tile;
     constexpr bool USES_RES = (F & (F_RES | F_KEEP | F_ZERO)) != 0;
-    float *res = USES_RES ? a.residual[p] + tile_lo : nullptr;
-    W *snd = (F & F_SEND) ? static_cast<W *>(a.sendbuf[p]) + slot * a.tile : nullptr;
-    GradSrc<GT> src{nullptr, nullptr, nullptr, 0};
+    float *res = USES_RES ? f.res_p + tile_lo + lo : nullptr;
+    W *snd = (F & F_SEND) ? static_cast<W *>(f.snd_p) + slot * a.tile + lo : nullptr;
     if constexpr ((F & F_G) == 0) {
-        run<F, W, GT, NT, U>(src, res, snd, tile_len, true, a.S, a.mu, l1);
+        run<F, W, GT, NT, U>([](GradSrc<GT> &) { return 1; }, res, snd, len, a.S, a.mu, l1);
         return;
     }
     if (!a.use_pieces) {
-        src.base = static_cast<const GT *>(a.tab[p]) + tile_lo;
-        run<F, W, GT, NT, U>(src, res, snd, tile_len, gf_aligned(src.base, GALIGN), a.S, a.mu, l1);
+        run<F, W, GT, NT, U>([&](GradSrc<GT> &src) {
+            src.base = f.pool_p + tile_lo + lo;
+            return gf_aligned(src.base, GALIGN) ? 1 : 0;
+        }, res, snd, len, a.S, a.mu, l1);
         return;
     }
-    const int ps = a.piece_start[tile], np = a.piece_start[tile + 1] - ps;
     const GT *const *tab = reinterpret_cast<const GT *const *>(a.tab) + static_cast<int64_t>(p) * a.tab_stride;
-    if (np == 1) {
-        const gf_piece pc = a.pieces[ps];
-        src.base = tab[pc.tensor] + pc.src_off;
-        run<F, W, GT, NT, U>(src, res, snd, tile_len, gf_aligned(src.base, GALIGN), a.S, a.mu, l1);
+    if (f.us.tensor >= 0) {                                // the whole range lies inside one tensor
+        run<F, W, GT, NT, U>([&](GradSrc<GT> &src) {
+            src.base = tab[f.us.tensor] + f.us.src_off;
+            return gf_aligned(src.base, GALIGN) ? 1 : 0;
+        }, res, snd, len, a.S, a.mu, l1);
         return;
     }
-    if (np <= MAX_FLAT_PIECES) {
-        // Several tensors meet in this tile: publish where each piece lives, then
-        // sweep the tile as if it were one run.
-        __shared__ const GT *s_ptr[MAX_FLAT_PIECES];
-        __shared__ int s_end[MAX_FLAT_PIECES];
+    __shared__ const GT *s_ptr[MAX_FLAT_PIECES];
+    __shared__ int s_end[MAX_FLAT_PIECES];
+    int ps = 0, pe = 0;
+    bool used_lds = false;
+    const bool done = run<F, W, GT, NT, U>([&](GradSrc<GT> &src) {
+        // pieces of the tile that reach into [lo, lo + len)
+        ps = a.piece_start[tile]; pe = a.piece_start[tile + 1];
+        if (a.subs > 1) {
+            while (ps < pe && a.pieces[ps].dst_rel + a.pieces[ps].len <= lo) ++ps;
+            while (pe > ps && a.pieces[pe - 1].dst_rel >= lo + len) --pe;
+        }
+        const int np = pe - ps;
+        if (np > MAX_FLAT_PIECES) return -1;
+        // Several tensors meet in this run: publish where each piece lives, then sweep
+        // it as if it were one run.
         int misaligned = 0;
         if (static_cast<int>(threadIdx.x) < np) {
             const gf_piece pc = a.pieces[ps + threadIdx.x];
             const GT *q = tab[pc.tensor] + pc.src_off;
-            s_ptr[threadIdx.x] = q - pc.dst_rel;
-            s_end[threadIdx.x] = pc.dst_rel + pc.len;
+            s_ptr[threadIdx.x] = q - (pc.dst_rel - lo);          // element x of the range is s_ptr[i][x]
+            s_end[threadIdx.x] = pc.dst_rel + pc.len - lo;
             misaligned = !gf_aligned(q, GALIGN) || (pc.dst_rel & 3);
         }
         const bool vec = !__syncthreads_or(misaligned);
         src.ptr = s_ptr; src.end = s_end; src.n = np;
-        run<F, W, GT, NT, U>(src, res, snd, tile_len, vec, a.S, a.mu, l1);
-        __syncthreads();                       // the table is reused by the next caller
-        return;
-    }
-    for (int i = ps; i < ps + np; ++i) {
+        used_lds = true;
+        return vec ? 1 : 0;
+    }, res, snd, len, a.S, a.mu, l1);
+    if (used_lds) __syncthreads();             // the table is reused by the next caller
+    if (done) return;
+    for (int i = ps; i < pe; ++i) {
         const gf_piece pc = a.pieces[i];
-        src.base = tab[pc.tensor] + pc.src_off;
-        run<F, W, GT, NT, U>(src, USES_RES ? res + pc.dst_rel : nullptr, (F & F_SEND) ? snd + pc.dst_rel : nullptr,
-                         pc.len, gf_aligned(src.base, GALIGN), a.S, a.mu, l1);
+        const int b = pc.dst_rel > lo ? pc.dst_rel : lo;                       // clipped to the range
+        const int e = pc.dst_rel + pc.len < lo + len ? pc.dst_rel + pc.len : lo + len;
+        run<F, W, GT, NT, U>([&](GradSrc<GT> &src) {
+            src.base = tab[pc.tensor] + pc.src_off + (b - pc.dst_rel);
+            return gf_aligned(src.base, GALIGN) ? 1 : 0;
+        }, USES_RES ? res + (b - lo) : nullptr, (F & F_SEND) ? snd + (b - lo) : nullptr, e - b, a.S, a.mu, l1);
     }
 }
 
-// One workgroup per (worker, tile).  WPE caps the wavefronts resident per SIMD
-// (0 = no cap): fewer resident workgroups mean fewer DRAM pages open at once,
-// which the in-place read-read-write stream of short tiles rewards.
+// One workgroup per (worker, tile, sub-tile).  WPE caps the wavefronts resident
+// per SIMD (0 = no cap): fewer resident workgroups mean fewer DRAM pages open at
+// once, which the in-place read-read-write stream rewards.
 template <int MODE, typename W, typename GT, int NT, int U, int WPE>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE ? WPE : 1, WPE ? WPE : 8)))
 void k_fuse(const FuseArgs a)
 {
-    const int p = blockIdx.x / a.units;
-    const int u = blockIdx.x - p * a.units;
+    const uint32_t item = xcd_order(blockIdx.x, a.total, a.grp_shift);
+    const uint32_t per_worker = static_cast<uint32_t>(a.units) * static_cast<uint32_t>(a.subs);
+    const int p = item / per_worker;
+    const uint32_t r = item - p * per_worker;
+    const int u = a.subs == 1 ? r : r / a.subs;
+    const int sub = a.subs == 1 ? 0 : r - u * a.subs;
     int tile = u;
     int64_t slot = u;
     if constexpr (MODE == MODE_PACK) {
         if (a.sel_idx) tile = a.sel_idx[u];
-    } else if constexpr (MODE == MODE_FUSED || MODE == MODE_SCALE) {
-        if (a.slotmap) slot = a.slotmap[tile];
     }
+    // One round of table look-ups, issued together.  Unused entries read a valid dummy
+    // location instead of branching, so that none of them waits for another.
+    Fetched<GT> f;
+    constexpr bool HAS_RES = MODE != MODE_DENSE, HAS_SND = MODE == MODE_FUSED || MODE == MODE_DENSE || MODE == MODE_PACK;
+    constexpr bool HAS_G = MODE == MODE_ACCUM || MODE == MODE_FUSED || MODE == MODE_DENSE;
+    const int32_t *slot_at = a.piece_start;                  // always a readable int32
+    if constexpr (MODE == MODE_FUSED || MODE == MODE_SCALE) {
+        if (a.slotmap) slot_at = a.slotmap + tile;
+    }
+    const int32_t slot_read = *slot_at;
+    f.res_p = HAS_RES ? a.residual[p] : nullptr;
+    f.snd_p = HAS_SND ? a.sendbuf[p] : nullptr;
+    f.pool_p = HAS_G ? static_cast<const GT *>(a.tab[static_cast<int64_t>(p) * a.tab_stride]) : nullptr;
+    f.us = gf_unit_src{0, -1, 0};
+    if constexpr (HAS_G) f.us = a.unit_src[static_cast<int64_t>(tile) * a.subs + sub];
+    if constexpr (MODE == MODE_FUSED || MODE == MODE_SCALE) {
+        if (a.slotmap) slot = slot_read;
+    }
+    const int64_t left = a.N - static_cast<int64_t>(tile) * a.tile;
+    const int tile_len = left < a.tile ? static_cast<int>(left) : a.tile;
+    const int lo = sub * a.sub;                               // may lie past a short last tile
+    int len = tile_len - lo;
+    len = len < 0 ? 0 : (len < a.sub ? len : a.sub);
     double l1 = 0.0;
-    if constexpr (MODE == MODE_ACCUM) tile_body<F_G | F_RES | F_KEEP | F_L1, W, GT, NT, U>(a, p, tile, 0, l1);   // mu = 1 here
+    if constexpr (MODE == MODE_ACCUM) tile_body<F_G | F_RES | F_KEEP | F_L1, W, GT, NT, U>(a, f, p, tile, 0, lo, len, l1);   // mu = 1 here
     if constexpr (MODE == MODE_FUSED) {
-        if (slot >= 0) tile_body<F_G | F_RES | F_SEND | F_ZERO | F_L1, W, GT, NT, U>(a, p, tile, slot, l1);
-        else tile_body<F_G | F_RES | F_KEEP | F_L1, W, GT, NT, U>(a, p, tile, 0, l1);
+        if (slot >= 0) tile_body<F_G | F_RES | F_SEND | F_ZERO | F_L1, W, GT, NT, U>(a, f, p, tile, slot, lo, len, l1);
+        else tile_body<F_G | F_RES | F_KEEP | F_L1, W, GT, NT, U>(a, f, p, tile, 0, lo, len, l1);
     }
-    if constexpr (MODE == MODE_DENSE) tile_body<F_G | F_SEND, W, GT, NT, U>(a, p, tile, slot, l1);
-    if constexpr (MODE == MODE_PACK) tile_body<F_RES | F_SEND | F_ZERO, W, GT, NT, U>(a, p, tile, slot, l1);
+    if constexpr (MODE == MODE_DENSE) tile_body<F_G | F_SEND, W, GT, NT, U>(a, f, p, tile, slot, lo, len, l1);
+    if constexpr (MODE == MODE_PACK) tile_body<F_RES | F_SEND | F_ZERO, W, GT, NT, U>(a, f, p, tile, slot, lo, len, l1);
     if constexpr (MODE == MODE_SCALE) {
-        if (slot < 0) tile_body<F_RES | F_KEEP, W, GT, NT, U>(a, p, tile, 0, l1);
+        if (slot < 0) tile_body<F_RES | F_KEEP, W, GT, NT, U>(a, f, p, tile, 0, lo, len, l1);
     }
     if constexpr (MODE == MODE_ACCUM || MODE == MODE_FUSED) {
         const double s = gf_block_sum<NT>(l1);
-        if (a.chunk_l1 && threadIdx.x == 0)
-            a.chunk_l1[static_cast<int64_t>(p) * a.n_tiles + tile] = static_cast<float>(s);
+        if (a.chunk_l1 && threadIdx.x == 0) {
+            const int64_t c = static_cast<int64_t>(p) * a.n_tiles + tile;
+            if (a.subs == 1) a.chunk_l1[c] = static_cast<float>(s);
+            else a.l1_part[c * a.subs + sub] = s;
+        }
     }
+}
+
+// chunk_l1[c] = sum of the chunk's sub-tile norms, first sub-tile first (fp64), rounded once.
+__global__ __launch_bounds__(GF_BLOCK) void k_l1_combine(const double *__restrict__ part, int64_t n, int32_t subs,
+                                                         float *__restrict__ chunk_l1)
+{
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * GF_BLOCK + threadIdx.x;
+    if (c >= n) return;
+    double s = part[c * subs];
+    for (int i = 1; i < subs; ++i) s += part[c * subs + i];
+    chunk_l1[c] = static_cast<float>(s);
 }
 
 // slotmap[c] = rank of chunk c in the ascending selection, or -1.
@@ -271,10 +395,13 @@ __global__ __launch_bounds__(GF_BLOCK) void k_slotmap(const int32_t *__restrict_
 }
 
 template <int MODE, int NT, int U, int WPE>
-gf_status launch_shape(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
+gf_status launch_shape(const gf_plan *pl, FuseArgs a, int grp_shift, hipStream_t st)
 {
-    const int64_t blocks = static_cast<int64_t>(a.units) * pl->P;
+    const int64_t blocks = static_cast<int64_t>(a.units) * a.subs * pl->P;
     if (blocks <= 0) return GF_OK;
+    if (blocks > (int64_t{1} << 30)) return GF_EINVAL;
+    a.total = static_cast<uint32_t>(blocks);
+    a.grp_shift = grp_shift;
     const dim3 grid(static_cast<unsigned>(blocks)), block(NT);
     // fp16 gradients only matter to the modes that read gradients
     constexpr bool READS_G = MODE == MODE_ACCUM || MODE == MODE_FUSED || MODE == MODE_DENSE;
@@ -293,21 +420,25 @@ gf_status launch_shape(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
     return GF_OK;
 }
 
-// Workgroup shape (measured on MI355X, P = 8..64 workers).  The in-place
-// accumulate stream does best when a long tile is swept by 1024 threads that
-// issue all 16 loads of a 32768-element stretch before the first store, and a
-// short tile by small workgroups with 8 loads in flight per thread and two
-// workgroups resident per SIMD set.  The dense cast (read fp32, write fp16
-// elsewhere) prefers full occupancy.
+// Workgroup shape (measured on MI355X, P = 8..64 workers, scattered tensors and
+// pools, with the XCD-ordered work list): 256 threads that issue all 16 loads of
+// an 8192-element sub-tile before the first store, two workgroups resident per
+// SIMD set, runs of 32 sub-tiles (1 MB of a worker's pool) per XCD.
+#ifndef GF_FUSE_GRP_SHIFT
+#define GF_FUSE_GRP_SHIFT 5
+#endif
+#ifndef GF_DENSE_GRP_SHIFT
+#define GF_DENSE_GRP_SHIFT 5
+#endif
 template <int MODE>
 gf_status launch(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
 {
 #if defined(GF_FUSE_NT)
-    return launch_shape<MODE, GF_FUSE_NT, GF_FUSE_U, GF_FUSE_WPE>(pl, a, st);
+    return launch_shape<MODE, GF_FUSE_NT, GF_FUSE_U, GF_FUSE_WPE>(pl, a, GF_FUSE_GRP_SHIFT, st);
 #else
-    if constexpr (MODE == MODE_DENSE) return launch_shape<MODE, 512, 4, 0>(pl, a, st);
-    if (pl->tile > 16384) return launch_shape<MODE, 1024, 8, 0>(pl, a, st);
-    return launch_shape<MODE, 256, 8, 2>(pl, a, st);
+    if constexpr (MODE == MODE_DENSE) return launch_shape<MODE, 256, 8, 2>(pl, a, GF_DENSE_GRP_SHIFT, st);
+    if (a.sub <= 4096) return launch_shape<MODE, 256, 4, 2>(pl, a, GF_FUSE_GRP_SHIFT, st);
+    return launch_shape<MODE, 256, 8, 2>(pl, a, GF_FUSE_GRP_SHIFT, st);
 #endif
 }
 
@@ -331,7 +462,9 @@ extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
     if (chunk_l1 && !accum) return GF_EINVAL;
     if (sel_idx && pack && (k < 1 || k > pl->n_chunks)) return GF_EINVAL;
     const bool need_map = sel_idx && pack && (accum || mu != 1.0f);
-    if (need_map && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return GF_EINVAL;
+    const int32_t subs = gf_fuse_subs(pl);
+    const bool need_part = chunk_l1 && subs > 1;
+    if ((need_map || need_part) && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return GF_EINVAL;
     if (!pl->on_device) return GF_ESTATE;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -344,12 +477,24 @@ extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
     a.chunk_l1 = chunk_l1;
     a.piece_start = pl->d_piece_start;
     a.pieces = pl->d_pieces;
+    a.unit_src = pl->d_unit_src;
     a.N = pl->N;
     a.tile = pl->tile;
     a.n_tiles = pl->n_tiles;
     a.units = pl->n_tiles;
+    a.sub = pl->tile < GF_FUSE_SUB ? pl->tile : GF_FUSE_SUB;
+    a.subs = subs;
+    if (need_part) a.l1_part = reinterpret_cast<double *>(static_cast<char *>(workspace) + gf_ws_l1part_off(pl));
     a.S = loss_scale;
     a.mu = mu;
+    const int64_t n_norms = static_cast<int64_t>(pl->P) * pl->n_tiles;
+    auto combine = [&](gf_status rc) {
+        if (rc != GF_OK || !need_part) return rc;
+        hipLaunchKernelGGL(k_l1_combine, dim3(static_cast<unsigned>((n_norms + GF_BLOCK - 1) / GF_BLOCK)), dim3(GF_BLOCK),
+                           0, st, a.l1_part, n_norms, subs, chunk_l1);
+        GF_LAUNCH_CHECK();
+        return GF_OK;
+    };
 
     int32_t *slotmap = nullptr;
     if (need_map) {
@@ -361,12 +506,12 @@ extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
 
     if (accum && !pack) {
         a.mu = 1.0f;                         // hg <- acc
-        return launch<MODE_ACCUM>(pl, a, st);
+        return combine(launch<MODE_ACCUM>(pl, a, st));
     }
     if (accum && pack) {
         if (!residual) return launch<MODE_DENSE>(pl, a, st);
         a.slotmap = slotmap;                 // null: every chunk is sent, rank = chunk index
-        return launch<MODE_FUSED>(pl, a, st);
+        return combine(launch<MODE_FUSED>(pl, a, st));
     }
     // pack only: visit the selected chunks; the rest only if mu scales them
     a.sel_idx = sel_idx;

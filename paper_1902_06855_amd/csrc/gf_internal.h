@@ -18,6 +18,13 @@
 #endif
 constexpr int32_t GF_DENSE_TILE = GF_DENSE_TILE_ELEMS;
 
+// gf_fuse_pack cuts tiles longer than this into sub-tiles of this many elements
+// (a multiple of 4), one workgroup each.
+#ifndef GF_FUSE_SUB_ELEMS
+#define GF_FUSE_SUB_ELEMS 8192
+#endif
+constexpr int32_t GF_FUSE_SUB = GF_FUSE_SUB_ELEMS;
+
 // One contiguous run of a tensor inside a tile (pool order).
 struct gf_piece {
     int64_t src_off;   // first element inside the tensor
@@ -27,6 +34,15 @@ struct gf_piece {
     int32_t pad_;
 };
 static_assert(sizeof(gf_piece) == 24, "piece record layout");
+
+// Where the gradients of one sub-tile of gf_fuse_pack live when they lie inside a
+// single tensor (the common case): saves the walk through the piece table.
+struct gf_unit_src {
+    int64_t src_off;   // first element inside the tensor
+    int32_t tensor;    // 0-based ID index, or -1: several tensors meet in this sub-tile
+    int32_t pad_;
+};
+static_assert(sizeof(gf_unit_src) == 16, "unit source record layout");
 
 // Ring work item of a dense plan: one workgroup's share of one segment of one
 // bucket.  (A workgroup never straddles segments, so the fold's starting
@@ -54,6 +70,7 @@ struct gf_plan {
     std::vector<int64_t> bucket_lo, bucket_hi;   // generation order
     std::vector<int32_t> piece_start;            // [n_tiles + 1]
     std::vector<gf_piece> pieces;
+    std::vector<gf_unit_src> unit_src;           // [n_tiles * gf_fuse_subs]
     std::vector<gf_bucket_dev> buckets;
     std::vector<gf_ring_block> ring_blocks;      // dense plans only
     // device (valid once on_device)
@@ -61,6 +78,7 @@ struct gf_plan {
     int device = -1;
     int32_t *d_piece_start = nullptr;
     gf_piece *d_pieces = nullptr;
+    gf_unit_src *d_unit_src = nullptr;
     gf_bucket_dev *d_buckets = nullptr;
     gf_ring_block *d_ring_blocks = nullptr;
 };
@@ -118,9 +136,22 @@ inline size_t gf_ws_scores_bytes(const gf_plan *p)
 {
     return (static_cast<size_t>(p->n_chunks) * sizeof(float) + 255) / 256 * 256;
 }
+// Sub-tiles per tile in gf_fuse_pack, and the partial chunk norms they leave
+// behind (one double per worker, chunk and sub-tile) when there are several.
+inline int32_t gf_fuse_subs(const gf_plan *p)
+{
+    return p->tile <= GF_FUSE_SUB ? 1 : (p->tile + GF_FUSE_SUB - 1) / GF_FUSE_SUB;
+}
+inline size_t gf_ws_l1part_off(const gf_plan *p) { return gf_ws_slotmap_bytes(p) + gf_ws_scores_bytes(p); }
+inline size_t gf_ws_l1part_bytes(const gf_plan *p)
+{
+    const int32_t subs = gf_fuse_subs(p);
+    if (p->chunk == 0 || subs == 1) return 0;
+    return (static_cast<size_t>(p->P) * p->n_chunks * subs * sizeof(double) + 255) / 256 * 256;
+}
 inline size_t gf_ws_total_bytes(const gf_plan *p)
 {
-    return gf_ws_slotmap_bytes(p) + gf_ws_scores_bytes(p) + 256;
+    return gf_ws_slotmap_bytes(p) + gf_ws_scores_bytes(p) + gf_ws_l1part_bytes(p) + 256;
 }
 
 #endif  // GF_INTERNAL_H

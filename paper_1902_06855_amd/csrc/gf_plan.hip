@@ -114,6 +114,29 @@ static gf_status build_plan(gf_plan *pl, const int64_t *numel, int32_t m, int64_
     }
     for (int32_t t = 0; t < pl->n_tiles; ++t) pl->piece_start[t + 1] += pl->piece_start[t];
 
+    // Sub-tiles of gf_fuse_pack that lie inside one tensor: where they start in it.
+    const int32_t subs = gf_fuse_subs(pl);
+    const int32_t sub_len = pl->tile < GF_FUSE_SUB ? pl->tile : GF_FUSE_SUB;
+    pl->unit_src.assign(static_cast<size_t>(pl->n_tiles) * subs, gf_unit_src{0, -1, 0});
+    for (int32_t t = 0; t < pl->n_tiles; ++t) {
+        const int64_t tile_lo = static_cast<int64_t>(t) * pl->tile;
+        const int64_t tile_len = std::min<int64_t>(pl->tile, pl->N - tile_lo);
+        for (int32_t sb = 0; sb < subs; ++sb) {
+            const int64_t lo = static_cast<int64_t>(sb) * sub_len;
+            const int64_t hi = std::min<int64_t>(tile_len, lo + sub_len);
+            if (hi <= lo) continue;
+            for (int32_t i = pl->piece_start[t]; i < pl->piece_start[t + 1]; ++i) {
+                const gf_piece &pc = pl->pieces[i];
+                if (pc.dst_rel <= lo && pc.dst_rel + pc.len >= hi) {
+                    gf_unit_src &us = pl->unit_src[static_cast<size_t>(t) * subs + sb];
+                    us.tensor = pc.tensor;
+                    us.src_off = pc.src_off + (lo - pc.dst_rel);
+                    break;
+                }
+            }
+        }
+    }
+
     pl->ring_M = P;
     return build_ring_tables(pl);
 }
@@ -157,9 +180,10 @@ static void free_device(gf_plan *pl)
 {
     if (pl->d_piece_start) (void)hipFree(pl->d_piece_start);
     if (pl->d_pieces) (void)hipFree(pl->d_pieces);
+    if (pl->d_unit_src) (void)hipFree(pl->d_unit_src);
     if (pl->d_buckets) (void)hipFree(pl->d_buckets);
     if (pl->d_ring_blocks) (void)hipFree(pl->d_ring_blocks);
-    pl->d_piece_start = nullptr; pl->d_pieces = nullptr;
+    pl->d_piece_start = nullptr; pl->d_pieces = nullptr; pl->d_unit_src = nullptr;
     pl->d_buckets = nullptr; pl->d_ring_blocks = nullptr;
     pl->on_device = false;
 }
@@ -171,6 +195,7 @@ extern "C" gf_status gf_plan_to_device(gf_plan *pl)
     GF_HIP_TRY(hipGetDevice(&pl->device));
     gf_status st = upload(&pl->d_piece_start, pl->piece_start);
     if (st == GF_OK) st = upload(&pl->d_pieces, pl->pieces);
+    if (st == GF_OK) st = upload(&pl->d_unit_src, pl->unit_src);
     if (st == GF_OK) st = upload(&pl->d_buckets, pl->buckets);
     if (st == GF_OK) st = upload(&pl->d_ring_blocks, pl->ring_blocks);
     if (st != GF_OK) { free_device(pl); return st; }

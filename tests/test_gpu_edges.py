@@ -116,3 +116,17 @@ def test_short_power_of_two_chunks_swept_several_at_a_time(gfm, chunk, mode):
         _run_csc(gfm, w, schedule, mode, T=3)
     w32 = _wl(sizes, 2, chunk, 0.3, wire="f32")
     _run_csc(gfm, w32, "lagged", mode, T=2)
+
+
+@pytest.mark.parametrize("chunk", [20000, 32000, 8200, 40001])
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+def test_long_chunks_cut_into_sub_tiles(gfm, chunk, mode):
+    """Chunks longer than a workgroup's share are swept by several workgroups: ragged last
+    sub-tiles, tensor borders and unaligned tensors inside sub-tiles, a short last chunk that
+    ends before some of its sub-tiles begin, chunk lengths that are no multiple of four."""
+    sizes = [chunk * 2 + 4, 100, 7, chunk + 8192, 33, 5000, chunk * 3, 9000, 8192 * 3, 50]
+    w = _wl(sizes, 3, chunk, 0.4)
+    for schedule in ("lagged", "immediate"):
+        _run_csc(gfm, w, schedule, mode, T=3)
+    w16 = _wl([s // 4 * 4 for s in sizes], 2, chunk, 0.4, wire="f32")
+    _run_csc(gfm, w16, "lagged", mode, T=2)
