@@ -30,9 +30,9 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
 # profiles/.  Keyed by workload; absent -> null in the JSON.
 MEASURED_TRAFFIC_BYTES = {
-    # k_fuse<MODE_FUSED>: FETCH 3 883 899.2 x 2.0000 KiB + WRITE 4 002 749.7 x 1.0000 KiB per launch
+    # k_fuse<MODE_FUSED>: FETCH 3 820 996.6 x 2.0000 KiB + WRITE 4 002 746.6 x 1.0000 KiB per launch
     # (profiles/k_fuse_fused_alexnet_csc.md); counted between L2 and the fabric
-    "alexnet_csc": 7954067914 + 4098815664,
+    "alexnet_csc": 7825400947 + 4098812480,
 }
 
 

@@ -55,22 +55,10 @@ struct FuseArgs {
     float S, mu;
 };
 
-constexpr int N_XCD = 8;
-
 // 1: issue the first batch of historical-gradient loads before the gradients' address is known
 #ifndef GF_FUSE_PREFETCH
 #define GF_FUSE_PREFETCH 1
 #endif
-
-// Work item of a workgroup: the hardware hands workgroup b to XCD b mod 8, so item
-// numbers are dealt in runs of 2^grp_shift per XCD.  A permutation of [0, total).
-__device__ __forceinline__ uint32_t xcd_order(uint32_t b, uint32_t total, int grp_shift)
-{
-    const uint32_t span = static_cast<uint32_t>(N_XCD) << grp_shift;
-    if (b >= total / span * span) return b;                 // ragged end: identity
-    const uint32_t x = b % N_XCD, i = b / N_XCD;
-    return ((i >> grp_shift) * span) + (x << grp_shift) + (i & ((1u << grp_shift) - 1u));
-}
 
 template <int F, typename W>
 __device__ __forceinline__ void elem4(const gf_f32x4 g, const gf_f32x4 r, gf_f32x4 &res_out,
@@ -314,7 +302,7 @@ template <int MODE, typename W, typename GT, int NT, int U, int WPE>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE ? WPE : 1, WPE ? WPE : 8)))
 void k_fuse(const FuseArgs a)
 {
-    const uint32_t item = xcd_order(blockIdx.x, a.total, a.grp_shift);
+    const uint32_t item = gf_xcd_order(blockIdx.x, a.total, a.grp_shift);
     const uint32_t per_worker = static_cast<uint32_t>(a.units) * static_cast<uint32_t>(a.subs);
     const int p = item / per_worker;
     const uint32_t r = item - p * per_worker;

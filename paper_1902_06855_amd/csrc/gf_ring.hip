@@ -19,6 +19,11 @@
 
 namespace {
 
+// log2 of the consecutive workgroups (8 KB of every send buffer each) one XCD takes
+#ifndef GF_RING_GRP_SHIFT
+#define GF_RING_GRP_SHIFT 5
+#endif
+
 // A dense plan's send buffers (P * N wire elements) are far larger than the
 // caches and are read exactly once: they are streamed.  The packed buffer of a
 // CSC plan was written just before by gf_fuse_pack and is still cache-resident:
@@ -84,8 +89,9 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
     const int M = HIER ? a.M : P;     // segments per bucket
     int64_t lo, hi, seg;
     int s, bis;
+    const uint32_t item = gf_xcd_order(blockIdx.x, gridDim.x, GF_RING_GRP_SHIFT);
     if constexpr (DENSE) {
-        const gf_ring_block rb = a.blocks[blockIdx.x];
+        const gf_ring_block rb = a.blocks[item];
         const gf_bucket_dev bk = a.buckets[rb.bucket];
         lo = bk.lo; hi = bk.hi; seg = bk.seg;
         s = rb.segment; bis = rb.block_in_segment;
@@ -97,8 +103,8 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
         int64_t L = a.L;
         if (a.L_dev) { const int64_t d = *a.L_dev; L = d < 0 ? 0 : (d < L ? d : L); }
         const int per_bucket = M * a.blocks_per_segment;
-        const int b = blockIdx.x / per_bucket;
-        const int r = blockIdx.x - b * per_bucket;
+        const int b = item / per_bucket;
+        const int r = item - b * per_bucket;
         lo = static_cast<int64_t>(b) * a.bucket_span;
         if (lo >= L) return;
         hi = lo + a.bucket_span < L ? lo + a.bucket_span : L;

@@ -25,6 +25,11 @@ struct UnpackArgs {
     float alpha, momentum, lr;
 };
 
+// log2 of the consecutive tiles one XCD takes
+#ifndef GF_UNPACK_GRP_SHIFT
+#define GF_UNPACK_GRP_SHIFT 4
+#endif
+
 // One contiguous run.  dst may be null in the update variant (gradient not kept).
 template <typename W, bool UPD, int NT>
 __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, float *w_, int len,
@@ -105,7 +110,7 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
 template <typename W, bool UPD, int NT>
 __global__ __launch_bounds__(NT) void k_unpack(const UnpackArgs a)
 {
-    const int j = blockIdx.x;
+    const int j = gf_xcd_order(blockIdx.x, gridDim.x, GF_UNPACK_GRP_SHIFT);
     const int tile = a.sel_idx ? a.sel_idx[j] : j;
     const int64_t tile_lo = static_cast<int64_t>(tile) * a.tile;
     const int64_t left = a.N - tile_lo;
