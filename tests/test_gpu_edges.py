@@ -130,3 +130,57 @@ def test_long_chunks_cut_into_sub_tiles(gfm, chunk, mode):
         _run_csc(gfm, w, schedule, mode, T=3)
     w16 = _wl([s // 4 * 4 for s in sizes], 2, chunk, 0.4, wire="f32")
     _run_csc(gfm, w16, "lagged", mode, T=2)
+
+
+def test_fp16_gradients_at_two_byte_addresses_and_in_long_chunks(gfm):
+    """fp16 gradient tensors that are only 2-byte aligned (element-wise path), and fp16 gradients in
+    chunks long enough to be cut into sub-tiles."""
+    gf, pl = gfm
+    for sizes, chunk, shift in (([4096, 8192, 520], 1024, True), ([20000 * 2 + 8, 36, 9000, 20000], 20000, False)):
+        w = _wl(sizes, 2, chunk, 0.3)
+        nc = ob.n_chunks(w.N, w.chunk)
+        k = w.k_for(nc)
+        pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=k, schedule="lagged", grad="f16")
+        st = op.new_state(w.P, w.N)
+        for t in range(2):
+            g16 = [[x.to(torch.float16) for x in row] for row in wl.gradients(w, t)]
+            g32 = [[torch.from_numpy(ob.f16_to_f32(x.numpy().view(np.uint16))) for x in row] for row in g16]
+            if shift:
+                dev = [[torch.cat([torch.zeros(1 + (j + p) % 3, dtype=torch.float16), g]).cuda()[1 + (j + p) % 3:]
+                        for j, g in enumerate(row)] for p, row in enumerate(g16)]
+                assert any(x.data_ptr() % 8 for row in dev for x in row)
+            else:
+                dev = [[x.cuda() for x in row] for row in g16]
+            pipe.set_gradients(dev)
+            pipe.out_pool.fill_(-4.0)
+            pipe.step()
+            torch.cuda.synchronize()
+            out = np.full(w.N, np.float32(-4.0))
+            pools = np.stack([op.fuse([x.numpy() for x in row], w.sizes) for row in g32])
+            r = op.csc_iteration(st, pools, w.chunk, k, w.loss_scale, w.mu, "lagged", out=out)
+            assert np.array_equal(pipe.sel.cpu().numpy(), r["sel_next"]), f"t={t} selection"
+            same_bits(pipe.out_pool, out, f"t={t} out")
+            for p in range(w.P):
+                same_bits(pipe.residual[p], st.hg[p], f"t={t} hg[{p}]")
+
+
+def test_reduce_groups_are_fixed_once_the_tables_are_on_the_device(gfm):
+    gf, _ = gfm
+    plan = gf.Plan([4096], 1 << 40, 0, 8)                  # uploaded by the constructor
+    with pytest.raises(gf.GfError) as e:
+        plan.set_reduce_groups(2)
+    assert e.value.status == gf.GF_ESTATE
+    plan.set_grad_type(gf.GF_WIRE_F16)                      # host-side only: allowed at any time
+
+
+def test_hierarchical_order_with_one_rank_and_with_one_group(gfm):
+    gf, _ = gfm
+    rng = np.random.default_rng(9)
+    for P, M in ((1, 1), (5, 1), (5, 5)):
+        L = 3001
+        x = (rng.standard_normal((P, L)) * 2.0 ** rng.integers(-6, 6, size=(P, 1))).astype(np.float16).view(np.uint16)
+        plan = gf.Plan([4096], 1 << 40, 4096, P, groups=M)
+        red = torch.zeros(L, dtype=torch.float16, device="cuda")
+        gf.gf_ring_reduce_sim(plan, gf.ptr_table([torch.from_numpy(x[p].view(np.float16)).cuda() for p in range(P)]), L, red)
+        torch.cuda.synchronize()
+        same_bits(red.view(torch.int16), ob.hier_fold(x, M).view(np.int16), f"P={P} M={M}")
