@@ -59,7 +59,7 @@ def algorithmic_bytes(w, k_elems_L: int, schedule: str, sgd: bool = False):
 
 
 def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int, chunk=None,
-            all_stages: bool = False, sgd=None):
+            all_stages: bool = False, sgd=None, graph: bool = False):
     import torch
     from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
 
@@ -107,15 +107,31 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
         pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
     torch.cuda.synchronize()
     _, st_bytes = algorithmic_bytes(w, pipe.cap, schedule, sgd is not None)
-    # events bracket only the dominant kernel unless a per-stage breakdown is asked for: every
-    # event is a packet between two kernels and costs a few microseconds of the step
-    pipe.probe, pipe.probe_only = [], (None if all_stages else max(st_bytes, key=st_bytes.get))
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    probe, pipe.probe = pipe.probe, None
+    if graph:
+        # every iteration replayed as one HIP graph (one graph per resident gradient set: the
+        # tables are baked in); no events inside a graph, so no per-kernel times in this mode
+        graphs = []
+        for s in range(n_sets):
+            pipe.use_tables(*tables[s]); graphs.append(pipe.capture())
+        for s in range(n_sets):
+            graphs[s].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graphs[it % n_sets].replay(); it += 1
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        probe = []
+    else:
+        # events bracket only the dominant kernel unless a per-stage breakdown is asked for: every
+        # event is a packet between two kernels and costs a few microseconds of the step
+        pipe.probe, pipe.probe_only = [], (None if all_stages else max(st_bytes, key=st_bytes.get))
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        probe, pipe.probe = pipe.probe, None
 
     ms_per_step = (t1 - t0) * 1e3 / steps
     L = int(pipe.packed_len.item()) if w.chunk else w.N
@@ -247,6 +263,14 @@ def main() -> int:
         dom_b = r["stage_bytes"][r["dominant"]]
         others[nm]["dominant_gbs"] = dom_b / r["dominant_ms"] / 1e6
 
+    if not a.pmc_probe and a.others:
+        # the same iterations replayed as HIP graphs (no events inside: whole-iteration time only)
+        for nm in [a.workload] + [x for x in a.others.split(",") if x and x != a.workload and "dense" in x][:2]:
+            wo = wl.config(nm)
+            so = max(10, wo.iterations)
+            r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2, None, False, None, True)
+            others[nm + "+graph"] = {kk: r[kk] for kk in ("P", "N", "schedule", "ms_per_step", "gbs", "bytes_per_step")}
+            others[nm + "+graph"]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
     if w.chunk and not a.pmc_probe and a.others:
         # the same workload with Algorithm 1's SGD-update step fused into the unpack
         r = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk, a.stage_times, (0.9, -0.01))

@@ -190,6 +190,21 @@ class Pipeline:
         e1.record()
         self.probe.append((name, e0, e1))
 
+    def capture(self) -> "torch.cuda.CUDAGraph":
+        """Record one steady-state iteration, with the gradient tables and the k in use now, as a
+        HIP graph; `replay()` on the result then launches the whole iteration at once.  Every
+        launch of an iteration depends on the one before it, so the graph saves only the host's
+        share of the gaps between kernels.  Not for the bootstrap iteration of the lagged
+        schedule, nor while warm-up still changes k."""
+        if self.chunk and self.schedule == "lagged" and self.t == 0:
+            raise ValueError("the first iteration of the lagged schedule is not a steady-state one")
+        if self.probe is not None:
+            raise ValueError("event probes cannot be recorded into a graph")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step()
+        return graph
+
     def step(self) -> None:
         """One whole iteration on the current stream; returns without synchronising."""
         if not self.chunk:

@@ -731,3 +731,39 @@ def test_hierarchical_order_csc_iterations(gfm, schedule):
             same_bits(pipe.out_pool, out, f"t={t} out")
             nxt = r["sel_next"] if schedule == "lagged" else r["sel"]
             assert np.array_equal(pipe.sel.cpu().numpy(), nxt), f"t={t} selection"
+
+
+# ------------------------------------------------------------- iterations replayed as HIP graphs
+
+@pytest.mark.parametrize("kind", ["csc", "dense"])
+def test_graph_replays_match_eager_iterations(gfm, kind):
+    """A captured iteration, replayed several times with eager work and synchronisations in
+    between, gives what the same iterations give when launched one call at a time."""
+    gf, pl = gfm
+    w = wl.scaled(wl.config("tiny"), 4) if kind == "csc" else odd_workload(P=3, chunk=0)
+    k = w.k_for(ob.n_chunks(w.N, w.chunk)) if w.chunk else 0
+    mk = lambda: pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=k, schedule="lagged")
+    eager, graphed = mk(), mk()
+    dev = [to_dev(cpu_grads(w, t)) for t in range(3)]
+    for pipe in (eager, graphed):                          # iteration 0 (the lagged bootstrap) runs eagerly
+        pipe.set_gradients(dev[0])
+        pipe.step()
+    torch.cuda.synchronize()
+    graphs = []
+    for t in (1, 2):                                       # one graph per gradient set: tables are baked in
+        graphed.set_gradients(dev[t])
+        graphs.append((graphed.grads_tab, graphed.capture()))
+    for it in range(6):
+        t = 1 + it % 2
+        eager.set_gradients(dev[t])
+        eager.step()
+        graphs[t - 1][1].replay()
+        torch.cuda.synchronize()
+        scratch = torch.randn(1 << 16, device="cuda").sum().item()          # unrelated eager work in between
+        assert scratch == scratch
+        same_bits(graphed.out_pool, eager.out_pool.cpu().numpy(), f"replay {it} out")
+        same_bits(graphed.reduced.view(torch.int16), eager.reduced.view(torch.int16).cpu().numpy(), f"replay {it} reduced")
+        if w.chunk:
+            assert torch.equal(graphed.sel, eager.sel), f"replay {it} selection"
+            for p in range(w.P):
+                same_bits(graphed.residual[p], eager.residual[p].cpu().numpy(), f"replay {it} hg[{p}]")
