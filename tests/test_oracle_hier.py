@@ -1,9 +1,14 @@
 """Pins for the CPU checker's hierarchical allreduce (Section 2.4: group reduce to
 the master, ring allreduce among the masters, broadcast in the group)."""
+import json
+import os
+
 import numpy as np
 import pytest
 
 from oracle import binding as ob
+
+GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_facts.json")))
 
 
 def _rand_halves(rng, P, L, spread=6):
@@ -111,8 +116,9 @@ def test_message_sizes_and_traffic(P, M):
     _, sent = ob.hier_allreduce_hops(x, M, "f16")
     seg = ob.ring_segment(L, M, "f16")
     assert seg == L // M
-    if (P, M) == (16, 4):
-        assert seg == L * M // P                    # the text's formula in its own example
+    ex = GOLD["hierarchical_example"]
+    if (P, M) == (ex["N"], ex["M"]):
+        assert seg == L * M // P == L // 4          # the text's formula K*M/N in its own example
     for r in range(P):
         local = r % G
         if local == 0:
