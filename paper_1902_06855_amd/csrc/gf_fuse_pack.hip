@@ -188,13 +188,27 @@ __device__ __forceinline__ bool run(Resolve &&resolve, float *res_, W *snd_, int
                 if constexpr (F & F_SEND) gf_buf_st<GF_AUX_CACHED>(so, sb, (v + u * NT) * WB);
             }
         }
-        for (; v < nvec; v += NT) {
-            gf_f32x4 gg = {}, rr = {}, ro; W4 so;
-            if constexpr (F & F_G) gg = load_g(v);
-            if constexpr (F & F_RES) rr = gf_buf_ld128<GF_AUX_STREAM>(rb, v * 16);
-            elem4<F, W>(gg, rr, ro, so, S, mu, l1);
-            if constexpr (WRITES_RES) gf_buf_st<GF_AUX_STREAM>(ro, rb, v * 16);
-            if constexpr (F & F_SEND) gf_buf_st<GF_AUX_CACHED>(so, sb, v * WB);
+        if (v < nvec) {
+            // what is left is less than a full batch: the same batch with the lanes past the end
+            // switched off, so that a ragged run still has all its loads in flight at once
+            gf_f32x4 gg[U], rr[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                gg[u] = gf_f32x4{}; rr[u] = gf_f32x4{};
+                if (v + u * NT < nvec) {
+                    if constexpr (F & F_G) gg[u] = load_g(v + u * NT);
+                    if constexpr (F & F_RES) rr[u] = gf_buf_ld128<GF_AUX_STREAM>(rb, (v + u * NT) * 16);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (v + u * NT < nvec) {
+                    gf_f32x4 ro; W4 so;
+                    elem4<F, W>(gg[u], rr[u], ro, so, S, mu, l1);
+                    if constexpr (WRITES_RES) gf_buf_st<GF_AUX_STREAM>(ro, rb, (v + u * NT) * 16);
+                    if constexpr (F & F_SEND) gf_buf_st<GF_AUX_CACHED>(so, sb, (v + u * NT) * WB);
+                }
+            }
         }
     };
     if (src.n == 0) sweep(std::true_type{});
@@ -470,7 +484,7 @@ extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
     a.tile = pl->tile;
     a.n_tiles = pl->n_tiles;
     a.units = pl->n_tiles;
-    a.sub = pl->tile < GF_FUSE_SUB ? pl->tile : GF_FUSE_SUB;
+    a.sub = gf_fuse_sub_len(pl);
     a.subs = subs;
     if (need_part) a.l1_part = reinterpret_cast<double *>(static_cast<char *>(workspace) + gf_ws_l1part_off(pl));
     a.S = loss_scale;

@@ -142,6 +142,9 @@ inline int32_t gf_fuse_subs(const gf_plan *p)
 {
     return p->tile <= GF_FUSE_SUB ? 1 : (p->tile + GF_FUSE_SUB - 1) / GF_FUSE_SUB;
 }
+// Sub-tile length.  Sub-tiles of exactly GF_FUSE_SUB elements (the last one of a tile takes what
+// is left) measured faster than equal parts: their starts stay 128-byte aligned within the tile.
+inline int32_t gf_fuse_sub_len(const gf_plan *p) { return p->tile < GF_FUSE_SUB ? p->tile : GF_FUSE_SUB; }
 inline size_t gf_ws_l1part_off(const gf_plan *p) { return gf_ws_slotmap_bytes(p) + gf_ws_scores_bytes(p); }
 inline size_t gf_ws_l1part_bytes(const gf_plan *p)
 {

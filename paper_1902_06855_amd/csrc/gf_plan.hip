@@ -116,7 +116,7 @@ static gf_status build_plan(gf_plan *pl, const int64_t *numel, int32_t m, int64_
 
     // Sub-tiles of gf_fuse_pack that lie inside one tensor: where they start in it.
     const int32_t subs = gf_fuse_subs(pl);
-    const int32_t sub_len = pl->tile < GF_FUSE_SUB ? pl->tile : GF_FUSE_SUB;
+    const int32_t sub_len = gf_fuse_sub_len(pl);
     pl->unit_src.assign(static_cast<size_t>(pl->n_tiles) * subs, gf_unit_src{0, -1, 0});
     for (int32_t t = 0; t < pl->n_tiles; ++t) {
         const int64_t tile_lo = static_cast<int64_t>(t) * pl->tile;
