@@ -15,8 +15,17 @@ __global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1
 {
     const int c = blockIdx.x * GF_BLOCK + threadIdx.x;
     if (c >= nc) return;
+    // rows are added in ascending order; eight loads are in flight at a time
     double s = 0.0;
-    for (int p = 0; p < P; ++p) s += static_cast<double>(l1[static_cast<int64_t>(p) * nc + c]);
+    int p = 0;
+    for (; p + 8 <= P; p += 8) {
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = l1[static_cast<int64_t>(p + u) * nc + c];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += static_cast<double>(x[u]);
+    }
+    for (; p < P; ++p) s += static_cast<double>(l1[static_cast<int64_t>(p) * nc + c]);
     score[c] = static_cast<float>(s);
 }
 
