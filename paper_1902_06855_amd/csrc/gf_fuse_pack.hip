@@ -14,9 +14,9 @@
 //
 // Workgroups are dealt to the eight XCDs round-robin by the hardware, and each
 // XCD has its own L2.  The work list is therefore permuted so that a run of
-// consecutive sub-tiles (a few hundred KB of one worker's pool) is handled by
-// one XCD: consecutive 32 KB sub-tiles spread over all XCDs use only part of
-// each L2's channels and stream measurably slower.
+// consecutive sub-tiles (1 MB of one worker's pool) is handled by one XCD:
+// consecutive 32 KB sub-tiles spread over all XCDs use only part of each L2's
+// channels and stream measurably slower.
 #include <type_traits>
 
 #include "gf_device.h"
