@@ -155,6 +155,21 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     return res
 
 
+def stream_probe():
+    """What bare kernels of the same access mixes sustain on this GPU (a stand-alone executable
+    that shares nothing with the library): context for the roofline fraction.  None if absent."""
+    import json as _json
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_1902_06855_amd", "probe", "stream_probe.bin")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        return _json.loads(r.stdout.strip().splitlines()[-1]) if r.returncode == 0 else None
+    except Exception:
+        return None
+
+
 def cpu_baseline(name: str, schedule: str, threads: int):
     """The CPU checker, as it stands, on host cores: one whole steady-state iteration of the same
     workload with the worker count cut down so that the run stays bounded.  Timed twice on the
@@ -300,6 +315,9 @@ def main() -> int:
                      "avg_launch_ms": main_res["dominant_ms"],
                      "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload)},
     }
+    if not a.pmc_probe:
+        # a child process, run after the timed work (5 GB of its own buffers)
+        out["roofline"]["bare_kernel_reference"] = stream_probe()
     if not a.no_cpu_baseline:
         ncpu = min(16, os.cpu_count() or 1)
         out["cpu_baseline"] = cpu_baseline(a.workload, a.schedule, ncpu)
