@@ -10,6 +10,8 @@
 //   read      sum of a            (4 B read per element)
 //   inplace   r += g              (8 B read, 4 B written: the accumulate pass)
 //   cast      h = fp16(g)         (4 B read, 2 B written elsewhere: the dense cast)
+//   fold8     out = x0 + ... + x7 (eight fp16 streams read at the same offset, one
+//                                  written: the ring fold of eight workers)
 // Output: one JSON object on stdout.
 #include <hip/hip_runtime.h>
 
@@ -80,6 +82,46 @@ void k_probe(const float *g, float *r, uint16_t *h, float *sink, long n_tiles, i
     if (PAT == READ) {
         const float s = acc.x + acc.y + acc.z + acc.w;
         if (s == 12345.678f) sink[0] = s;          // keeps the loads alive
+    }
+}
+
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t add_h2(uint32_t a, uint32_t b)
+{
+    const h2v s = __builtin_bit_cast(h2v, a) + __builtin_bit_cast(h2v, b);
+    return __builtin_bit_cast(uint32_t, s);
+}
+
+constexpr int FOLD_P = 8, FOLD_NT = 512;
+
+// 512 threads, 16 bytes of every stream per thread: all eight loads in flight, then the fold.
+__global__ __launch_bounds__(FOLD_NT) void k_fold(const uint16_t *const *streams, uint16_t *out, long n_blocks, int grp)
+{
+    const long blk = xcd_order(blockIdx.x, n_blocks, grp);
+    const long e0 = blk * FOLD_NT * 8;
+    u4 x[FOLD_P];
+#pragma unroll
+    for (int q = 0; q < FOLD_P; ++q) {
+        const __amdgpu_buffer_rsrc_t d = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(streams[q]) + e0, 0, FOLD_NT * 16, 0x00020000);
+        x[q] = __builtin_amdgcn_raw_buffer_load_b128(d, threadIdx.x * 16, 0, AUX);
+    }
+    u4 v = x[0];
+#pragma unroll
+    for (int q = 1; q < FOLD_P; ++q) {
+        v.x = add_h2(v.x, x[q].x); v.y = add_h2(v.y, x[q].y); v.z = add_h2(v.z, x[q].z); v.w = add_h2(v.w, x[q].w);
+    }
+    const __amdgpu_buffer_rsrc_t od = __builtin_amdgcn_make_buffer_rsrc(out + e0, 0, FOLD_NT * 16, 0x00020000);
+    __builtin_amdgcn_raw_buffer_store_b128(v, od, threadIdx.x * 16, 0, 0);
+}
+
+__global__ void k_fill_h(uint16_t *x, long n, unsigned seed)
+{
+    long i = blockIdx.x * static_cast<long>(blockDim.x) + threadIdx.x;
+    const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+    for (; i < n; i += stride) {
+        unsigned v = static_cast<unsigned>(i) * 2654435761u + seed;
+        v ^= v >> 15; v *= 2246822519u; v ^= v >> 13;
+        x[i] = static_cast<uint16_t>(0x2000u + (v & 0x0fffu));      // small positive halves
     }
 }
 
@@ -154,11 +196,36 @@ int main(int argc, char **argv)
             }
         }
     }
+    // eight separately allocated fp16 streams of n / 8 elements each, one output
+    const long nh = n / 8 / (FOLD_NT * 8 * 64) * (FOLD_NT * 8 * 64);
+    const uint16_t *hs[FOLD_P];
+    for (int q = 0; q < FOLD_P; ++q) {
+        uint16_t *p;
+        CK(hipMalloc(&p, nh * 2));
+        hipLaunchKernelGGL(k_fill_h, dim3(2048), dim3(256), 0, 0, p, nh, 11u + q);
+        hs[q] = p;
+    }
+    const uint16_t **d_hs;
+    uint16_t *fold_out;
+    CK(hipMalloc(&d_hs, sizeof(hs)));
+    CK(hipMalloc(&fold_out, nh * 2));
+    CK(hipMemcpy(d_hs, hs, sizeof(hs), hipMemcpyHostToDevice));
+    CK(hipDeviceSynchronize());
+    const long fold_blocks = nh / (FOLD_NT * 8);
+    double fold_best = 0;
+    int fold_grp = 0;
+    for (int grp = 0; grp <= 6; grp += 2) {
+        const double ms = time_ms([&] { hipLaunchKernelGGL(k_fold, dim3(static_cast<unsigned>(fold_blocks)), dim3(FOLD_NT), 0, 0, d_hs, fold_out, fold_blocks, grp); }, reps);
+        const double gbs = 2.0 * nh * (FOLD_P + 1) / ms / 1e6;
+        if (gbs > fold_best) { fold_best = gbs; fold_grp = grp; }
+    }
     std::printf("{\"elements\": %ld, \"tile\": %ld, \"unit\": \"GB/s\", "
-                "\"read\": %.1f, \"read_shape\": \"runs of %d tiles per XCD, %d waves per SIMD\", "
+                "\"fold8\": %.1f, \"fold8_shape\": \"8 fp16 streams of %ld elements, runs of %d blocks per XCD\", ",
+                n, TILE, fold_best, nh, 1 << fold_grp);
+    std::printf("\"read\": %.1f, \"read_shape\": \"runs of %d tiles per XCD, %d waves per SIMD\", "
                 "\"inplace\": %.1f, \"inplace_shape\": \"runs of %d tiles per XCD, %d waves per SIMD\", "
                 "\"cast\": %.1f, \"cast_shape\": \"runs of %d tiles per XCD, %d waves per SIMD\"}\n",
-                n, TILE, best[READ], 1 << best_grp[READ], best_wpe[READ],
+                best[READ], 1 << best_grp[READ], best_wpe[READ],
                 best[INPLACE], 1 << best_grp[INPLACE], best_wpe[INPLACE],
                 best[CAST], 1 << best_grp[CAST], best_wpe[CAST]);
     return 0;
