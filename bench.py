@@ -155,6 +155,39 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     return res
 
 
+def run_overlap(name: str, steps: int, warmup: int, n_streams: int = 2):
+    """A dense workload with every lazy-allreduce bucket issued on its own (cast, ring, cast back)
+    on side streams in generation order: the enable-overlap setting, with nothing to overlap
+    with here, so this shows what issuing bucket by bucket costs."""
+    import torch
+    from paper_1902_06855_amd import pipeline as pl, workloads as wl
+
+    w = wl.config(name)
+    torch.cuda.set_device(0)
+    sig = wl.sigma_table(w)
+    ov = pl.OverlappedDense(w.sizes, w.P, w.theta, w.loss_scale, wire=w.wire, n_streams=n_streams)
+    sets, tabs = [], []
+    for s in range(2):
+        g = wl.gradients(w, s, device="cuda", sig=sig)
+        ov.set_gradients(g)
+        sets.append(g); tabs.append(ov.grad_tabs)
+    it = 0
+    for _ in range(warmup):
+        ov.grad_tabs = tabs[it % 2]; ov.step(); it += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ov.grad_tabs = tabs[it % 2]; ov.step(); it += 1
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    total, _ = algorithmic_bytes(w, w.N, "dense")
+    res = {"P": w.P, "N": w.N, "n_buckets": ov.n_buckets, "streams": n_streams, "ms_per_step": ms,
+           "gbs": total / ms / 1e6, "bytes_per_step": total, "frac_of_hbm_peak": total / ms / 1e6 / HBM_PEAK_GBS}
+    del ov, sets, tabs
+    torch.cuda.empty_cache()
+    return res
+
+
 def stream_probe():
     """What bare kernels of the same access mixes sustain on this GPU (a stand-alone executable
     that shares nothing with the library): context for the roofline fraction.  None if absent."""
@@ -286,6 +319,9 @@ def main() -> int:
             r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2, None, False, None, True)
             others[nm + "+graph"] = {kk: r[kk] for kk in ("P", "N", "schedule", "ms_per_step", "gbs", "bytes_per_step")}
             others[nm + "+graph"]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
+    if a.ladder and not a.pmc_probe:
+        for nm in ("alexnet_dense", "resnet50_dense_4mb"):
+            others[nm + "+buckets_on_side_streams"] = run_overlap(nm, 10, 5)
     if w.chunk and not a.pmc_probe and a.others:
         # the same workload with Algorithm 1's SGD-update step fused into the unpack
         r = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk, a.stage_times, (0.9, -0.01))

@@ -220,3 +220,82 @@ class Pipeline:
             self._run("fused", self.fused); self._run("ring", self.ring); self._run("unpack", self.unpack)
             self._run("select", self.select, True)
         self.t += 1
+
+
+class OverlappedDense:
+    """The enable-overlap setting of lazy allreduce (Sections 2.6 and 3.1): every bucket is cast,
+    reduced and cast back on its own, on side streams, in the order backward produces the
+    buckets (tensor m first), each as soon as its gradients are there, instead of one pass over
+    the whole pool after backward.
+
+    A bucket holds whole tensors and is one contiguous range of the pool, so it is a dense plan of
+    its own over those tensors; the same entry points are called with pointers that start at the
+    bucket.  The results are those of the single-pass `Pipeline` bit for bit (every bucket is its
+    own ring there as well).  It computes nothing itself."""
+
+    def __init__(self, sizes: Sequence[int], P: int, theta: int, loss_scale: float, wire: str = "f16",
+                 n_streams: int = 2, device: str = "cuda", grad: str = "f32", groups: int = 0):
+        self.sizes, self.P, self.S, self.device = list(sizes), int(P), float(loss_scale), device
+        self.alpha = float(np.float32(1.0) / np.float32(loss_scale))
+        self.wire = gf.GF_WIRE_F16 if wire == "f16" else gf.GF_WIRE_F32
+        self.wdtype = torch.float16 if wire == "f16" else torch.float32
+        whole = gf.Plan(self.sizes, min(int(theta), 1 << 60), 0, self.P, self.wire, to_device=False)
+        self.N, self.m = whole.N, len(self.sizes)
+        self.off, self.lo, self.hi = whole.layout()
+        whole.close()
+        new = lambda n, dt: torch.zeros(n, dtype=dt, device=device)
+        self.send = [new(self.N, self.wdtype) for _ in range(self.P)]
+        self.reduced = new(self.N, self.wdtype)
+        self.out_pool = new(self.N, torch.float32)
+        # tensors of bucket b, ID order: those whose pool offset lies in [lo, hi)
+        self.members = [[j for j in range(self.m) if lo <= self.off[j] < hi] for lo, hi in zip(self.lo, self.hi)]
+        self.plans = []
+        for mem in self.members:
+            plan = gf.Plan([self.sizes[j] for j in mem], 1 << 60, 0, self.P, self.wire, groups=groups)
+            if grad == "f16":
+                plan.set_grad_type(gf.GF_WIRE_F16)
+            self.plans.append(plan)
+        self.send_tabs = [gf.ptr_table([s[lo:] for s in self.send], device) for lo in self.lo]
+        self.streams = [torch.cuda.Stream(device=device) for _ in range(max(1, int(n_streams)))]   # default priority
+        self.grad_tabs = self.pool_tabs = None
+        self._keep = None
+
+    @property
+    def n_buckets(self) -> int:
+        return len(self.lo)
+
+    def set_gradients(self, grads: List[List[torch.Tensor]]) -> None:
+        """grads[p][l]: scattered device tensors in ID order."""
+        self._keep = grads
+        self.grad_tabs = [gf.ptr_table([grads[p][j] for p in range(self.P) for j in mem], self.device)
+                          for mem in self.members]
+        self.pool_tabs = None
+
+    def set_pools(self, pools: List[torch.Tensor]) -> None:
+        """pools[p]: N-element pools in generation order (read in place, bucket by bucket)."""
+        self._keep = pools
+        self.pool_tabs = [gf.ptr_table([q[lo:] for q in pools], self.device) for lo in self.lo]
+        self.grad_tabs = None
+
+    def step(self, ready: Optional[Sequence[torch.cuda.Event]] = None) -> None:
+        """Issue every bucket in generation order.  ready[b], if given, is an event recorded once
+        the gradients of bucket b exist (by whatever produces them); bucket b waits for it alone.
+        Returns without synchronising; the current stream waits for all buckets."""
+        cur = torch.cuda.current_stream()
+        start = torch.cuda.Event()
+        start.record(cur)
+        for b, plan in enumerate(self.plans):
+            s = self.streams[b % len(self.streams)]
+            s.wait_event(start)
+            if ready is not None:
+                s.wait_event(ready[b])
+            lo, hi = self.lo[b], self.hi[b]
+            with torch.cuda.stream(s):
+                gf.gf_fuse_pack(plan, gf.GF_PHASE_ACCUM | gf.GF_PHASE_PACK,
+                                grads=self.grad_tabs[b] if self.grad_tabs else None,
+                                pools=self.pool_tabs[b] if self.pool_tabs else None,
+                                loss_scale=self.S, sendbuf=self.send_tabs[b])
+                gf.gf_ring_reduce_sim(plan, self.send_tabs[b], hi - lo, self.reduced[lo:])
+                gf.gf_unpack_apply(plan, self.reduced[lo:], hi - lo, alpha=self.alpha, out_pool=self.out_pool[lo:])
+        for s in self.streams:
+            cur.wait_stream(s)

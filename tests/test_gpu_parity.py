@@ -767,3 +767,39 @@ def test_graph_replays_match_eager_iterations(gfm, kind):
             assert torch.equal(graphed.sel, eager.sel), f"replay {it} selection"
             for p in range(w.P):
                 same_bits(graphed.residual[p], eager.residual[p].cpu().numpy(), f"replay {it} hg[{p}]")
+
+
+# ------------------------------------------- buckets issued one by one on side streams (overlap)
+
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+def test_buckets_issued_on_side_streams_equal_the_single_pass(gfm, mode, wire):
+    gf, pl = gfm
+    for w, theta in ((odd_workload(P=3, chunk=0, wire=wire), 1000), (odd_workload(P=4, chunk=0, wire=wire), 0),
+                     (wl.Workload("even", [4096, 64, 8192, 1000, 24, 16384], P=2, chunk=0, density=1.0,
+                                  loss_scale=32.0, theta=5000, wire=wire), 5000)):
+        grads = cpu_grads(w, 0)
+        pools = pools_np(grads, w.sizes)
+        ref = op.dense_iteration(pools, w.sizes, theta, w.loss_scale, wire)
+        ov = pl.OverlappedDense(w.sizes, w.P, theta, w.loss_scale, wire=wire, n_streams=3)
+        assert ov.n_buckets == len(ref["bucket_lo"]) and ov.lo == list(ref["bucket_lo"])
+        dev = to_dev(grads)
+        dev_pools = [torch.from_numpy(pools[p]).cuda() for p in range(w.P)]
+        if mode == "gather":
+            ov.set_gradients(dev)
+        else:
+            ov.set_pools(dev_pools)
+        ready = [torch.cuda.Event() for _ in range(ov.n_buckets)]    # one arrival event per bucket
+        ov.step(ready=None)
+        torch.cuda.synchronize()
+        it, nt = (torch.int16, np.int16) if wire == "f16" else (torch.int32, np.int32)
+        for p in range(w.P):
+            same_bits(ov.send[p].view(it), ref["send"][p].view(nt), f"send[{p}] theta={theta}")
+        same_bits(ov.reduced.view(it), ref["reduced"].view(nt), f"reduced theta={theta}")
+        same_bits(ov.out_pool, ref["out"], f"out theta={theta}")
+        ov.out_pool.fill_(-1.0)
+        for e in reversed(ready):
+            e.record()
+        ov.step(ready=ready)
+        torch.cuda.synchronize()
+        same_bits(ov.out_pool, ref["out"], f"out with arrival events theta={theta}")
