@@ -218,9 +218,13 @@ gf_status gf_chunk_score_select(const gf_plan *plan, const float *chunk_l1,
  *     x_s[i] + x_{s+1}[i] + ... + x_{s-1}[i]      (worker indices mod P)
  * rounded to the wire type after every addition, which is what P-1
  * reduce-scatter hops produce when rank r first sends its segment r to rank
- * r+1; the all-gather hops are copies.
+ * r+1; the all-gather hops are copies.  After gf_plan_set_reduce_groups the
+ * order is the hierarchical one described there (group chains, then the ring
+ * over the masters, M segments instead of P).
  *
- * sendbuf: device table [P] of wire-typed buffers of L elements.
+ * sendbuf: device table [P] of wire-typed buffers of L elements, only read
+ *   (for a dense plan on an fp16 wire they may be the workers' fp16 gradient
+ *   pools themselves: Section 3.1's allreduce directly on the memory pool).
  * CSC plan: the packed buffer [0, L) is reduced bucket by bucket, each bucket
  *   a ring of its own (Section 3.2: CSC starts an allreduce once the buffer
  *   holds more than theta): packed chunks are taken in order and a bucket
