@@ -803,3 +803,32 @@ def test_buckets_issued_on_side_streams_equal_the_single_pass(gfm, mode, wire):
         ov.step(ready=ready)
         torch.cuda.synchronize()
         same_bits(ov.out_pool, ref["out"], f"out with arrival events theta={theta}")
+
+
+def test_a_bucket_waits_for_its_own_gradients_only(gfm):
+    """Gradients are written bucket by bucket on a producer stream (as backward would), each bucket
+    followed by its arrival event; the buckets' own streams must not read them earlier."""
+    gf, pl = gfm
+    sizes = [1 << 20, 1 << 18, 3000, 1 << 20, 1 << 16]
+    w = wl.Workload("arrive", sizes, P=2, chunk=0, density=1.0, loss_scale=16.0, theta=1 << 17)
+    grads = cpu_grads(w, 0)
+    ref = op.dense_iteration(pools_np(grads, w.sizes), w.sizes, w.theta, w.loss_scale)
+    ov = pl.OverlappedDense(w.sizes, w.P, w.theta, w.loss_scale, n_streams=2)
+    assert ov.n_buckets >= 3
+    staged = to_dev(grads)
+    live = [[torch.zeros_like(x) for x in row] for row in staged]        # what the buckets read
+    ov.set_gradients(live)
+    torch.cuda.synchronize()
+    producer = torch.cuda.Stream()
+    ready = [torch.cuda.Event() for _ in range(ov.n_buckets)]
+    with torch.cuda.stream(producer):
+        for b, mem in enumerate(ov.members):                              # generation order
+            for _ in range(20):                                           # make the producer slow
+                for p in range(w.P):
+                    for j in mem:
+                        live[p][j].copy_(staged[p][j], non_blocking=True)
+            ready[b].record(producer)
+    ov.step(ready=ready)
+    torch.cuda.synchronize()
+    same_bits(ov.reduced.view(torch.int16), ref["reduced"].view(np.int16), "reduced")
+    same_bits(ov.out_pool, ref["out"], "out")
