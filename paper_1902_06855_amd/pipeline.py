@@ -299,3 +299,11 @@ class OverlappedDense:
                 gf.gf_unpack_apply(plan, self.reduced[lo:], hi - lo, alpha=self.alpha, out_pool=self.out_pool[lo:])
         for s in self.streams:
             cur.wait_stream(s)
+
+    def capture(self) -> "torch.cuda.CUDAGraph":
+        """The whole bucket-by-bucket iteration (side streams forked from and joined to the current
+        one, no arrival events) as one HIP graph: takes the host's launch rate out of the picture."""
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step()
+        return graph

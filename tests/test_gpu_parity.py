@@ -832,3 +832,27 @@ def test_a_bucket_waits_for_its_own_gradients_only(gfm):
     torch.cuda.synchronize()
     same_bits(ov.reduced.view(torch.int16), ref["reduced"].view(np.int16), "reduced")
     same_bits(ov.out_pool, ref["out"], "out")
+
+
+def test_bucket_wise_iteration_replayed_as_a_graph(gfm):
+    """Fork to the side streams and join back inside one captured graph; replays with eager work in
+    between equal the single pass."""
+    gf, pl = gfm
+    w = odd_workload(P=3, chunk=0)
+    ref = [op.dense_iteration(pools_np(cpu_grads(w, t), w.sizes), w.sizes, 300, w.loss_scale) for t in range(2)]
+    ov = pl.OverlappedDense(w.sizes, w.P, 300, w.loss_scale, n_streams=3)
+    assert ov.n_buckets > 3
+    graphs, keep = [], []
+    for t in range(2):
+        dev = to_dev(cpu_grads(w, t))
+        ov.set_gradients(dev)
+        keep.append((dev, ov.grad_tabs))
+        graphs.append(ov.capture())
+    for it in range(6):
+        t = it % 2
+        ov.out_pool.fill_(-2.0)
+        graphs[t].replay()
+        torch.cuda.synchronize()
+        torch.randn(1 << 14, device="cuda").sum().item()                     # unrelated eager work in between
+        same_bits(ov.reduced.view(torch.int16), ref[t]["reduced"].view(np.int16), f"replay {it} reduced")
+        same_bits(ov.out_pool, ref[t]["out"], f"replay {it} out")
