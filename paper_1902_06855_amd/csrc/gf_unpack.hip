@@ -90,10 +90,23 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
 #pragma unroll
         for (int u = 0; u < U; ++u) one(v + u * NT, x[u], hh[u], ww[u]);
     }
-    for (; v < nvec; v += NT) {
-        gf_f32x4 hh = {}, ww = {};
-        if constexpr (UPD) { hh = gf_buf_ld128<GF_AUX_STREAM>(hb, v * 16); ww = gf_buf_ld128<GF_AUX_STREAM>(wb, v * 16); }
-        one(v, ld_src(v), hh, ww);
+    if (v < nvec) {
+        // less than a full batch left: the same batch with the lanes past the end switched off
+        W4 x[U] = {};
+        gf_f32x4 hh[U] = {}, ww[U] = {};
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (v + u * NT < nvec) {
+                x[u] = ld_src(v + u * NT);
+                if constexpr (UPD) {
+                    hh[u] = gf_buf_ld128<GF_AUX_STREAM>(hb, (v + u * NT) * 16);
+                    ww[u] = gf_buf_ld128<GF_AUX_STREAM>(wb, (v + u * NT) * 16);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (v + u * NT < nvec) one(v + u * NT, x[u], hh[u], ww[u]);
     }
     for (int i = (nvec << 2) + threadIdx.x; i < len; i += NT) {
         const float g = gf_from_wire<W>(src[i]) * alpha;
