@@ -122,16 +122,17 @@ def test_dense_full_size_sampled(mods, name, groups):
 
 # --------------------------------------------------------------------- CSC
 
-@pytest.mark.parametrize("name", ["alexnet_csc", "resnet50_csc"])
-def test_csc_full_size_sampled(mods, name):
+@pytest.mark.parametrize("name,groups", [("alexnet_csc", 0), ("resnet50_csc", 0), ("alexnet_csc", 4), ("resnet50_csc", 8)])
+def test_csc_full_size_sampled(mods, name, groups):
     gf, pl = mods
     w = wl.config(name)
+    M = groups or w.P                                 # ranks in the ring: all, or the group masters
     P, N, C = w.P, w.N, w.chunk
     nc = ob.n_chunks(N, C)
     k = w.k_for(nc)
     sig = wl.sigma_table(w)
     gsets = [wl.gradients(w, t, device="cuda", sig=sig) for t in range(2)]
-    pipe = pl.Pipeline(w.sizes, P, C, w.theta, w.loss_scale, k=k, mu=w.mu, schedule="lagged")
+    pipe = pl.Pipeline(w.sizes, P, C, w.theta, w.loss_scale, k=k, mu=w.mu, schedule="lagged", groups=groups)
     assert pipe.n_chunks == nc
     sync = torch.cuda.synchronize
     alpha = np.float32(1.0) / np.float32(w.loss_scale)
@@ -170,7 +171,7 @@ def test_csc_full_size_sampled(mods, name):
         """send and historical gradient of the sampled chunks; returns {c: (hg, reduced or None, slot)}."""
         L = ob.packed_len(N, C, sel)
         assert int(pipe.packed_len.item()) == L
-        seg = ob.ring_segment(L, P)
+        seg = ob.ring_segment(L, M)
         state = {}
         for c in chunks:
             sent, j = is_in(sel, c)
@@ -181,7 +182,8 @@ def test_csc_full_size_sampled(mods, name):
             if sent:
                 got = np.stack([pipe.send[p][j * C:j * C + n].cpu().numpy() for p in range(P)])
                 assert np.array_equal(u16(got), send_c), f"t={t} send of chunk {c}"
-                red = fold_in_ring_order(send_c, (j * C + np.arange(n)) // seg)
+                where = (j * C + np.arange(n)) // seg
+                red = fold_in_hierarchical_order(send_c, where, M) if groups else fold_in_ring_order(send_c, where)
             assert np.array_equal(u32(dev_chunk(pipe.residual, c)), u32(hg_c)), f"t={t} hg of chunk {c}"
             state[c] = (hg_c, red, j)
         return state
