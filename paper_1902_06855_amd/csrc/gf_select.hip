@@ -10,12 +10,32 @@ namespace {
 
 constexpr int SEL_T = 1024;   // threads of the single selecting workgroup
 
+// score[c]: chunks that went through this iteration's allreduce (c = prev_sel[j]) are scored by
+// the norm of the (identical) reduced values, each GPU dividing it by the GPU count before the
+// norms are summed over GPUs; every other chunk by the sum of the workers' local norms, rows
+// added in ascending order.
 __global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1, int32_t P, int32_t nc,
+                                                    const float *__restrict__ red_l1,
+                                                    const int32_t *__restrict__ prev_sel, int32_t k_prev,
                                                     float *__restrict__ score)
 {
     const int c = blockIdx.x * GF_BLOCK + threadIdx.x;
     if (c >= nc) return;
-    // rows are added in ascending order; eight loads are in flight at a time
+    if (prev_sel) {
+        int lo = 0, hi = k_prev;                  // first position with prev_sel[pos] >= c (ascending list)
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (prev_sel[mid] < c) lo = mid + 1; else hi = mid;
+        }
+        if (lo < k_prev && prev_sel[lo] == c) {
+            const double share = static_cast<double>(red_l1[lo]) / static_cast<double>(P);
+            double s = 0.0;
+            for (int p = 0; p < P; ++p) s += share;
+            score[c] = static_cast<float>(s);
+            return;
+        }
+    }
+    // eight row loads are in flight at a time
     double s = 0.0;
     int p = 0;
     for (; p + 8 <= P; p += 8) {
@@ -27,21 +47,6 @@ __global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1
     }
     for (; p < P; ++p) s += static_cast<double>(l1[static_cast<int64_t>(p) * nc + c]);
     score[c] = static_cast<float>(s);
-}
-
-// Chunks that went through this iteration's allreduce: each GPU divides the
-// norm of the (identical) reduced values by the GPU count, then the norms are
-// summed over GPUs.
-__global__ __launch_bounds__(GF_BLOCK) void k_score_sent(const float *__restrict__ red_l1,
-                                                         const int32_t *__restrict__ prev_sel, int32_t k_prev,
-                                                         int32_t P, float *__restrict__ score)
-{
-    const int j = blockIdx.x * GF_BLOCK + threadIdx.x;
-    if (j >= k_prev) return;
-    const double share = static_cast<double>(red_l1[j]) / static_cast<double>(P);
-    double s = 0.0;
-    for (int p = 0; p < P; ++p) s += share;
-    score[prev_sel[j]] = static_cast<float>(s);
 }
 
 // Monotone map from float order to unsigned order.
@@ -166,13 +171,8 @@ extern "C" gf_status gf_chunk_score_select(const gf_plan *pl, const float *chunk
     const int32_t nc = pl->n_chunks;
 
     hipLaunchKernelGGL(k_score, dim3((nc + GF_BLOCK - 1) / GF_BLOCK), dim3(GF_BLOCK), 0, st,
-                       chunk_l1, pl->P, nc, scores);
+                       chunk_l1, pl->P, nc, reduced_l1, prev_sel, k_prev, scores);
     GF_LAUNCH_CHECK();
-    if (prev_sel) {
-        hipLaunchKernelGGL(k_score_sent, dim3((k_prev + GF_BLOCK - 1) / GF_BLOCK), dim3(GF_BLOCK), 0, st,
-                           reduced_l1, prev_sel, k_prev, pl->P, scores);
-        GF_LAUNCH_CHECK();
-    }
     hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_T), 0, st,
                        scores, nc, k, pl->chunk, pl->N, sel_idx, mask, packed_len);
     GF_LAUNCH_CHECK();
