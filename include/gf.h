@@ -199,7 +199,8 @@ gf_status gf_fuse_pack(const gf_plan *plan, uint32_t phase,
  * GPU holds the same reduced values and divides its norm by the GPU count.
  * prev_sel NULL (k_prev ignored) scores every chunk by the first rule.
  * The k chunks with the largest score are chosen, equal scores going to the
- * lower chunk index.
+ * lower chunk index.  A score that is not a number ranks above every number
+ * (such chunks tie among themselves); -0 equals +0.
  *
  * chunk_l1 [P*n_chunks], reduced_l1 [k_prev], prev_sel [k_prev] ascending:
  *   device, in.   scores [n_chunks] fp32, sel_idx [k] int32 ascending,

@@ -5,13 +5,15 @@ Arrays are numpy, C-contiguous; fp16 data travels as uint16 bit patterns.
 from __future__ import annotations
 
 import ctypes as C
+import os
 from typing import Optional, Sequence, Tuple
 
 import numpy as np
 
 from . import build as _build
 
-_lib = C.CDLL(_build.build())
+# GF_ORACLE_LIB: another build of the same source (the sanitizer build the tests make)
+_lib = C.CDLL(os.environ.get("GF_ORACLE_LIB") or _build.build())
 
 _i32, _i64, _f32 = C.c_int32, C.c_int64, C.c_float
 _vp = C.c_void_p

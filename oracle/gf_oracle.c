@@ -274,14 +274,21 @@ void gfo_score(const float *l1f, int32_t P, int64_t nc,
 
 /* ------------------------------------------------ top-k chunks (Sec. 3.2)
  * The k chunks with the largest score; equal scores go to the lower chunk
- * index; the answer is listed in ascending chunk order. */
+ * index; the answer is listed in ascending chunk order.  The paper does not
+ * say what a chunk whose norm is not a number is worth; the reading taken is
+ * that it ranks above every number (a worker whose gradients overflowed gets
+ * them exchanged, as dense training would), all such chunks tying. */
 typedef struct { float s; int32_t c; } gfo_key;
 
 static int key_cmp(const void *a, const void *b)
 {
     const gfo_key *x = (const gfo_key *)a, *y = (const gfo_key *)b;
-    if (x->s > y->s) return -1;
-    if (x->s < y->s) return 1;
+    int xn = isnan(x->s), yn = isnan(y->s);
+    if (xn != yn) return xn ? -1 : 1;
+    if (!xn) {
+        if (x->s > y->s) return -1;
+        if (x->s < y->s) return 1;
+    }
     return (x->c > y->c) - (x->c < y->c);
 }
 

@@ -49,10 +49,13 @@ __global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1
     score[c] = static_cast<float>(s);
 }
 
-// Monotone map from float order to unsigned order.
+// Monotone map from float order to unsigned order.  A score that is not a number (of either
+// sign, any payload) gets the largest key: such chunks rank above every number and tie.
 __device__ __forceinline__ uint32_t ord_key(float f)
 {
-    const uint32_t b = __float_as_uint(f);
+    uint32_t b = __float_as_uint(f);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return 0xffffffffu;
+    if (b == 0x80000000u) b = 0;                             // -0 compares equal to +0
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 

@@ -57,6 +57,51 @@ def test_plan_matches_the_checker(name):
     plan.close()
 
 
+def _buckets_by_cumsum(sizes, theta):
+    """Section 3.1's rule stated without a running counter: a bucket that starts at pool offset
+    `start` ends at the first tensor border that lies more than theta beyond it (tensors in
+    generation order, the last ID first); what is left at the end is one more bucket."""
+    edges = np.concatenate([[0], np.cumsum(list(sizes)[::-1])])
+    out, start = [], 0
+    while start < edges[-1]:
+        beyond = edges[edges - start > theta]
+        end = int(beyond[0]) if len(beyond) else int(edges[-1])
+        out.append((start, end))
+        start = end
+    return out
+
+
+def test_plan_buckets_follow_the_threshold_rule_stated_on_cumulative_sizes():
+    rng = np.random.default_rng(11)
+    cases = [([5, 3, 4, 2], th) for th in (0, 1, 5, 6, 13, 14)]
+    cases += [([int(s) for s in rng.integers(1, 5000, size=int(rng.integers(1, 60)))], int(rng.integers(0, 12000)))
+              for _ in range(40)]
+    for name in ("alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb"):
+        w = wl.config(name)
+        cases.append((w.sizes, w.theta))
+    for sizes, theta in cases:
+        plan = gf.Plan(sizes, theta, 0, 2, to_device=False)
+        _, lo, hi = plan.layout()
+        assert list(zip(lo, hi)) == _buckets_by_cumsum(sizes, theta), (sizes[:8], theta)
+        plan.close()
+    # hand-worked (generation order 2, 4, 3, 5): theta 5 -> 6 | 8; theta 6 -> 9 | 5; strict ">"
+    for theta, want in ((5, [6, 8]), (6, [9, 5]), (13, [14]), (0, [2, 4, 3, 5]), (1, [2, 4, 3, 5])):
+        plan = gf.Plan([5, 3, 4, 2], theta, 0, 2, to_device=False)
+        _, lo, hi = plan.layout()
+        assert [b - a for a, b in zip(lo, hi)] == want
+        plan.close()
+
+
+def test_warmup_chunk_counts_hand_worked():
+    # sparsity ramps linearly: k = 1000 * (1 - 0.09 t); the double-precision product sits an ulp
+    # above 820 and 190 at t = 2 and t = 9 and must not round up to 821 / 191
+    plan = gf.Plan([1000 * 64], 1 << 40, 64, 2, to_device=False)
+    assert [plan.warmup_k(0.1, t, 10) for t in range(12)] == [1000, 910, 820, 730, 640, 550, 460, 370, 280, 190, 100, 100]
+    small = gf.Plan([100 * 8], 1 << 40, 8, 2, to_device=False)
+    assert small.warmup_k(0.07, 0, 0) == 7 and small.warmup_k(0.071, 0, 0) == 8
+    plan.close(); small.close()
+
+
 def test_warmup_schedule_matches_the_checker():
     plan = gf.Plan([1000 * 64], 1 << 40, 64, 2, to_device=False)
     for d, T in ((0.1, 10), (0.25, 4), (0.15, 7), (1.0, 5), (0.01, 0)):

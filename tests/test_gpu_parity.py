@@ -274,6 +274,30 @@ def test_select_bit_exact_including_ties(gfm, nc, k):
     assert np.array_equal(sel.cpu().numpy(), np.arange(k))
 
 
+def test_select_with_scores_that_are_not_numbers(gfm):
+    """Infinite and NaN norms (a worker whose gradients overflowed): NaN ranks above +inf above
+    every finite score, NaNs tie, the lower index wins; the choice equals the checker's."""
+    gf, _ = gfm
+    rng = np.random.default_rng(77)
+    P, C, nc = 2, 8, 3000
+    plan = gf.Plan([nc * C], 1 << 40, C, P)
+    l1 = rng.random((P, nc)).astype(np.float32)
+    l1[0, rng.integers(0, nc, size=40)] = np.inf
+    l1[1, rng.integers(0, nc, size=25)] = np.nan
+    l1[0, 5] = np.inf; l1[1, 5] = np.nan                  # inf + nan
+    sc = ob.score(l1)
+    assert np.isnan(sc).sum() >= 20 and np.isinf(sc).sum() >= 30
+    d_l1 = torch.from_numpy(l1).cuda().reshape(-1)
+    for k in (1, 10, int(np.isnan(sc).sum()), int(np.isnan(sc).sum()) + 7, 500, nc):
+        want, wmask = ob.select(sc, k)
+        sel = torch.zeros(k, dtype=torch.int32, device="cuda")
+        mask = torch.zeros(nc, dtype=torch.uint8, device="cuda")
+        gf.gf_chunk_score_select(plan, d_l1, k=k, sel_idx=sel, mask=mask, workspace=plan.workspace())
+        torch.cuda.synchronize()
+        assert np.array_equal(sel.cpu().numpy(), want), f"k={k}"
+        assert np.array_equal(mask.cpu().numpy(), wmask)
+
+
 @pytest.mark.parametrize("P,nc,k", [(6, 500, 50), (64, 20_000, 333)])   # the second takes the multi-kernel route
 def test_select_after_allreduce_scores_sent_chunks_by_their_reduced_norm(gfm, P, nc, k):
     gf, _ = gfm

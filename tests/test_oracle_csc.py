@@ -106,6 +106,30 @@ def test_select_special_cases():
     assert list(ob.select(z, 4)[0]) == [0, 1, 2, 3]          # all tied -> lowest indices
 
 
+def test_select_ranks_a_score_that_is_not_a_number_above_every_number():
+    # the reading taken for non-finite norms: NaN > +inf > finite, NaNs tie (lower index first)
+    inf, nan = np.float32(np.inf), np.float32(np.nan)
+    sc = np.array([1.0, nan, inf, 5.0, -nan, 0.0, inf, 2.0], dtype=np.float32)
+    assert list(ob.select(sc, 1)[0]) == [1]
+    assert list(ob.select(sc, 2)[0]) == [1, 4]
+    assert list(ob.select(sc, 3)[0]) == [1, 2, 4]
+    assert list(ob.select(sc, 4)[0]) == [1, 2, 4, 6]
+    assert list(ob.select(sc, 5)[0]) == [1, 2, 3, 4, 6]
+    assert list(ob.select(sc, 8)[0]) == list(range(8))
+    # against a full sort with that ranking spelled out, random positions
+    rng = np.random.default_rng(9)
+    for n in (9, 300):
+        s = rng.random(n).astype(np.float32)
+        s[rng.integers(0, n, size=n // 5)] = nan
+        s[rng.integers(0, n, size=n // 7)] = inf
+        rank = lambda c: (0, 0.0, c) if np.isnan(s[c]) else (1, -float(s[c]), c)
+        for k in (1, n // 4, n // 2, n):
+            want = sorted(sorted(range(n), key=rank)[:k])
+            assert list(ob.select(s, k)[0]) == want
+    z = np.array([0.0, -0.0, 0.0, -0.0], dtype=np.float32)       # -0 equals +0: index decides
+    assert list(ob.select(z, 2)[0]) == [0, 1]
+
+
 # ------------------------------------------------- pack + historical gradient
 
 @pytest.mark.parametrize("mu", [1.0, 0.9])
