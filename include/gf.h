@@ -40,9 +40,11 @@ typedef enum {
     GF_EINVAL = 1,   /* bad argument (null where required, out of range, wrong mode) */
     GF_ENOMEM = 2,   /* host or device allocation failed (plan calls only)          */
     GF_EHIP = 3,     /* a HIP runtime call or kernel launch failed                  */
-    GF_ESTATE = 4    /* plan in the wrong state: device tables missing (call
+    GF_ESTATE = 4,   /* plan in the wrong state: device tables missing (call
                         gf_plan_to_device), or already uploaded for a setter that
                         must run before                                             */
+    GF_ELIMIT = 5    /* the plan needs more scratch than the fixed array of
+                        gf_fuse_pack_static holds (use gf_fuse_pack)                */
 } gf_status;
 
 /* Element type of what travels between workers (Section 2.5: fp16 gradients go
@@ -188,6 +190,27 @@ gf_status gf_fuse_pack(const gf_plan *plan, uint32_t phase,
                        float loss_scale, float mu,
                        void *const *sendbuf, float *chunk_l1,
                        void *workspace, gf_stream stream);
+
+/* -------------------------------------------------------- gf_fuse_pack_static
+ * gf_fuse_pack for callers that can neither allocate device memory nor hand a
+ * workspace over: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results; the scratch (slot map, partial chunk norms) lives in a fixed device
+ * array of GF_STATIC_SCRATCH_BYTES that is part of the library's code object
+ * (every GPU the library runs on holds one copy until the process ends).  The
+ * call allocates nothing and frees nothing.
+ * GF_ELIMIT if gf_plan_workspace_bytes(plan) > GF_STATIC_SCRATCH_BYTES (nothing
+ * is launched); other errors as gf_fuse_pack.  All calls on one GPU share that
+ * GPU's array, which keeps the previous call's contents (every entry a call
+ * reads is written by that call first): two calls that overlap in time on one
+ * GPU, on different streams or from different threads, race. */
+#define GF_STATIC_SCRATCH_BYTES (4u << 20)
+gf_status gf_fuse_pack_static(const gf_plan *plan, uint32_t phase,
+                              const void *const *grads, const float *const *pools,
+                              float *const *residual,
+                              const int32_t *sel_idx, int32_t k,
+                              float loss_scale, float mu,
+                              void *const *sendbuf, float *chunk_l1, gf_stream stream);
 
 /* ------------------------------------------------------ gf_chunk_score_select
  * Section 3.2, important-chunk selection.  What the paper does with a small

@@ -17,6 +17,7 @@
 // consecutive sub-tiles (1 MB of one worker's pool) is handled by one XCD:
 // consecutive 32 KB sub-tiles spread over all XCDs use only part of each L2's
 // channels and stream measurably slower.
+#include <mutex>
 #include <type_traits>
 
 #include "gf_device.h"
@@ -446,6 +447,40 @@ gf_status launch(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
 
 }  // namespace
 
+// Scratch of gf_fuse_pack_static: one copy per GPU, part of the code object, held until the
+// process ends.  Host code never uses this name as an address; it asks the runtime where the
+// array lives on the current device and passes that pointer to the kernels.
+static __device__ __align__(256) unsigned char scratch[GF_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[MAX_DEVICES];        // device address of `scratch` on each GPU, once looked up
+
+// Address of this GPU's copy of `scratch` (looked up once per device, with that device current).
+gf_status static_scratch(void **out)
+{
+    int dev = -1;
+    GF_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return GF_EINVAL;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        GF_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return GF_EHIP;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return GF_OK;
+}
+
+gf_status fuse_pack(const gf_plan *pl, uint32_t phase, const void *const *grads, const float *const *pools,
+                    float *const *residual, const int32_t *sel_idx, int32_t k, float loss_scale, float mu,
+                    void *const *sendbuf, float *chunk_l1, void *workspace, gf_stream stream);
+
+}  // namespace
+
 extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
                                   const void *const *grads, const float *const *pools,
                                   float *const *residual,
@@ -453,6 +488,30 @@ extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
                                   float loss_scale, float mu,
                                   void *const *sendbuf, float *chunk_l1,
                                   void *workspace, gf_stream stream)
+{
+    return fuse_pack(pl, phase, grads, pools, residual, sel_idx, k, loss_scale, mu, sendbuf, chunk_l1, workspace, stream);
+}
+
+extern "C" gf_status gf_fuse_pack_static(const gf_plan *pl, uint32_t phase,
+                                         const void *const *grads, const float *const *pools,
+                                         float *const *residual,
+                                         const int32_t *sel_idx, int32_t k,
+                                         float loss_scale, float mu,
+                                         void *const *sendbuf, float *chunk_l1, gf_stream stream)
+{
+    if (!pl) return GF_EINVAL;
+    if (gf_ws_total_bytes(pl) > static_cast<size_t>(GF_STATIC_SCRATCH_BYTES)) return GF_ELIMIT;
+    void *ws = nullptr;
+    const gf_status rc = static_scratch(&ws);
+    if (rc != GF_OK) return rc;
+    return fuse_pack(pl, phase, grads, pools, residual, sel_idx, k, loss_scale, mu, sendbuf, chunk_l1, ws, stream);
+}
+
+namespace {
+
+gf_status fuse_pack(const gf_plan *pl, uint32_t phase, const void *const *grads, const float *const *pools,
+                    float *const *residual, const int32_t *sel_idx, int32_t k, float loss_scale, float mu,
+                    void *const *sendbuf, float *chunk_l1, void *workspace, gf_stream stream)
 {
     if (!pl) return GF_EINVAL;
     if (phase == 0 || (phase & ~(GF_PHASE_ACCUM | GF_PHASE_PACK))) return GF_EINVAL;
@@ -524,3 +583,5 @@ extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
     a.slotmap = slotmap;
     return launch<MODE_SCALE>(pl, a, st);
 }
+
+}  // namespace

@@ -27,7 +27,8 @@ if not os.path.exists(LIB_PATH):
 
 _lib = C.CDLL(LIB_PATH)
 
-GF_OK, GF_EINVAL, GF_ENOMEM, GF_EHIP, GF_ESTATE = 0, 1, 2, 3, 4
+GF_OK, GF_EINVAL, GF_ENOMEM, GF_EHIP, GF_ESTATE, GF_ELIMIT = 0, 1, 2, 3, 4, 5
+GF_STATIC_SCRATCH_BYTES = 4 << 20
 GF_WIRE_F16, GF_WIRE_F32 = 0, 1
 GF_PHASE_ACCUM, GF_PHASE_PACK = 1, 2
 
@@ -35,7 +36,8 @@ EXPORTS = (
     "gf_status_string", "gf_plan_create", "gf_plan_set_grad_type", "gf_plan_set_reduce_groups",
     "gf_plan_to_device", "gf_plan_destroy", "gf_plan_info",
     "gf_plan_layout", "gf_plan_ring_segment", "gf_plan_tiles", "gf_plan_tile_pieces",
-    "gf_plan_workspace_bytes", "gf_plan_warmup_k", "gf_fuse_pack", "gf_chunk_score_select", "gf_ring_reduce_sim",
+    "gf_plan_workspace_bytes", "gf_plan_warmup_k", "gf_fuse_pack", "gf_fuse_pack_static", "gf_chunk_score_select",
+    "gf_ring_reduce_sim",
     "gf_unpack_apply", "gf_unpack_sgd_update",
 )
 
@@ -64,6 +66,7 @@ _plan_tile_pieces = _sig("gf_plan_tile_pieces", _i32, _vp, _i32, _i32, C.POINTER
 _plan_workspace_bytes = _sig("gf_plan_workspace_bytes", C.c_size_t, _vp)
 _plan_warmup_k = _sig("gf_plan_warmup_k", _i32, _vp, C.c_double, _i64, _i64)
 _fuse_pack = _sig("gf_fuse_pack", C.c_int, _vp, _u32, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp, _vp)
+_fuse_pack_static = _sig("gf_fuse_pack_static", C.c_int, _vp, _u32, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp)
 _chunk_score_select = _sig("gf_chunk_score_select", C.c_int, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
                            _vp, _vp, _vp)
 _ring_reduce_sim = _sig("gf_ring_reduce_sim", C.c_int, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp)
@@ -199,6 +202,14 @@ def gf_fuse_pack(plan: Plan, phase: int, *, grads=None, pools=None, residual=Non
     _check(_fuse_pack(plan.handle, int(phase), _dptr(grads), _dptr(pools), _dptr(residual), _dptr(sel_idx),
                       int(k), float(loss_scale), float(mu), _dptr(sendbuf), _dptr(chunk_l1), _dptr(workspace),
                       _stream(stream)), "gf_fuse_pack")
+
+
+def gf_fuse_pack_static(plan: Plan, phase: int, *, grads=None, pools=None, residual=None, sel_idx=None, k: int = 0,
+                        loss_scale: float = 1.0, mu: float = 1.0, sendbuf=None, chunk_l1=None, stream=None) -> None:
+    """gf_fuse_pack with the library's own fixed scratch instead of a workspace (allocates nothing)."""
+    _check(_fuse_pack_static(plan.handle, int(phase), _dptr(grads), _dptr(pools), _dptr(residual), _dptr(sel_idx),
+                             int(k), float(loss_scale), float(mu), _dptr(sendbuf), _dptr(chunk_l1),
+                             _stream(stream)), "gf_fuse_pack_static")
 
 
 def gf_chunk_score_select(plan: Plan, chunk_l1, *, reduced_l1=None, prev_sel=None, k_prev: int = 0, k: int,

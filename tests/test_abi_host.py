@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    for code in range(5):
+    for code in range(6):
         assert gf.gf_status_string(code).startswith("GF_")
     assert "unknown" in gf.gf_status_string(99)
 
