@@ -9,15 +9,20 @@ unpack (gf_unpack_apply) and scoring / selection for the next iteration
 region.  The metric is algorithmic bytes per step / time per step (GB/s) and
 its share of the 8 TB/s HBM peak.
 
-Prints ONE JSON line.  `roofline` describes the dominant kernel, timed with
-events on the launch stream inside the timed region; `cpu_baseline` is the CPU
-checker run on the host cores on a bounded sample of the same workload.
+Prints ONE JSON line.  `value` comes from the wall clock around exactly K steps
+(synchronised on both sides); `median_ms` / `min_ms` from one event per
+iteration boundary on the launch stream; `roofline` describes the dominant
+kernel, bracketed by events on the launch stream inside the timed region;
+`config.stages` gives every stage's time and GB/s from a second, untimed pass
+with every stage bracketed; `cpu_baseline` is the CPU checker run on the host
+cores on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -26,14 +31,19 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
-# profiles/.  Keyed by workload; absent -> null in the JSON.
+# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (one FETCH_SIZE run,
+# one WRITE_SIZE run, each scaled by what the same counter reads for a copy of known size): bytes
+# read + bytes written between L2 and the fabric, from the tables under profiles/.  Keyed by
+# (workload, input layout, schedule): a run in any other configuration reports null.
 MEASURED_TRAFFIC_BYTES = {
-    # k_fuse<MODE_FUSED>: FETCH 3 820 996.6 x 2.0000 KiB + WRITE 4 002 746.6 x 1.0000 KiB per launch
-    # (profiles/k_fuse_fused_alexnet_csc.md); counted between L2 and the fabric
-    "alexnet_csc": 7825400947 + 4098812480,
+    # profiles/k_fuse_fused_alexnet_csc.md: FETCH 3 820 996.6 x 2 KiB + WRITE 4 002 746.6 KiB per launch
+    ("alexnet_csc", "gather", "lagged"): 7825400947 + 4098812480,
+    # profiles/kernel_stats_other_workloads.md, cast kernel: FETCH 969 289.3 x 2 KiB + WRITE 952 581.8 KiB
+    ("alexnet_dense", "gather", "dense"): 1985104486 + 975443763,
 }
+
+DEFAULT_WORKLOAD = "resnet50_csc"     # the largest single-GPU configuration of the five
+DEFAULT_OTHERS = "alexnet_csc,alexnet_dense,resnet50_dense_4mb,resnet50_dense_64mb,resnet50_csc_p1,alexnet_csc_p1"
 
 
 def algorithmic_bytes(w, k_elems_L: int, schedule: str, sgd: bool = False):
@@ -58,48 +68,73 @@ def algorithmic_bytes(w, k_elems_L: int, schedule: str, sgd: bool = False):
     return sum(st.values()), st
 
 
-def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int, chunk=None,
-            all_stages: bool = False, sgd=None, graph: bool = False):
+def resident_gradient_sets(w, n_sets: int, mode: str, few_dispatches: bool = False):
+    """n_sets gradient sets resident in HBM and their pointer tables: scattered per-tensor
+    allocations (mode "gather": fusion is folded into the read) or one pool per worker (mode
+    "pool": the zero-copy layout).  few_dispatches draws each worker's set with one generator
+    launch (the tensors are then slices of one allocation, still reached through the per-tensor
+    pointer table): for runs under a counter-collecting profiler, which must not see the tens of
+    thousands of small launches of the per-tensor generator."""
     import torch
-    from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
+    from paper_1902_06855_amd import gf, workloads as wl
 
-    w = wl.config(name)
-    if chunk:                      # tuning aid: same tensors, another chunk size
-        w.chunk = int(chunk)
-    if os.environ.get("GF_BENCH_P"):   # tuning aid: another worker count
-        w.P = int(os.environ["GF_BENCH_P"])
-    torch.cuda.set_device(0)
     sig = wl.sigma_table(w)
-    pipe_k = 0
-    probe_plan = gf.Plan(w.sizes, min(w.theta, 1 << 60), w.chunk, w.P, to_device=False)
-    if w.chunk:
-        pipe_k = w.k_for(probe_plan.n_chunks)
-    off, _, _ = probe_plan.layout()
-    probe_plan.close()
-    pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=pipe_k, mu=w.mu, wire=w.wire,
-                       schedule=schedule, sgd=sgd, grad=w.grad, zero_copy=bool(w.extra.get("zero_copy")),
-                       groups=int(w.extra.get("groups", 0)))
-    if w.extra.get("zero_copy"):
-        mode = "pool"
-    # gradient sets resident in HBM: scattered per-tensor allocations (fusion is folded into the
-    # read) or one pool per worker (the zero-copy layout)
+    plan = gf.Plan(w.sizes, min(w.theta, 1 << 60), w.chunk, w.P, to_device=False)
+    off, _, _ = plan.layout()
+    plan.close()
+    gdt = torch.float16 if w.grad == "f16" else torch.float32
     tables, keep = [], []
-    t_gen = time.perf_counter()
     for s in range(n_sets):
-        if mode == "gather":
+        if few_dispatches:
+            pools = []
+            for p in range(w.P):
+                g = torch.Generator(device="cuda")
+                g.manual_seed(wl.stream_seed(w.seed, s, p, 0xFEED))
+                x = torch.randn(w.N, generator=g, device="cuda", dtype=torch.float32)
+                x.mul_(float(sig[:, p].mean()))
+                pools.append(x.to(gdt))
+            keep.append(pools)
+            if mode == "gather":
+                tables.append((gf.ptr_table([pools[p][off[l]:off[l] + w.sizes[l]] for p in range(w.P)
+                                             for l in range(w.m)]), None))
+            else:
+                tables.append((None, gf.ptr_table(pools)))
+        elif mode == "gather":
             g = wl.gradients(w, s, device="cuda", sig=sig)
             keep.append(g)
             tables.append((gf.ptr_table([t for row in g for t in row]), None))
         else:
             pools = []
             for p in range(w.P):
-                pool = torch.empty(w.N, dtype=torch.float16 if w.grad == "f16" else torch.float32, device="cuda")
+                pool = torch.empty(w.N, dtype=gdt, device="cuda")
                 for l in range(w.m):
                     pool[off[l]:off[l] + w.sizes[l]] = wl.gradient_tensor(w, sig, s, p, l, "cuda")
                 pools.append(pool)
             keep.append(pools)
             tables.append((None, gf.ptr_table(pools)))
     torch.cuda.synchronize()
+    return tables, keep
+
+
+def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int,
+            sgd=None, graph: bool = False, few_dispatches: bool = False, stage_pass: bool = True):
+    import torch
+    from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
+
+    w = wl.config(name)
+    torch.cuda.set_device(0)
+    pipe_k = 0
+    if w.chunk:
+        probe_plan = gf.Plan(w.sizes, min(w.theta, 1 << 60), w.chunk, w.P, to_device=False)
+        pipe_k = w.k_for(probe_plan.n_chunks)
+        probe_plan.close()
+    pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=pipe_k, mu=w.mu, wire=w.wire,
+                       schedule=schedule, sgd=sgd, grad=w.grad, zero_copy=bool(w.extra.get("zero_copy")),
+                       groups=int(w.extra.get("groups", 0)))
+    if w.extra.get("zero_copy"):
+        mode = "pool"
+    t_gen = time.perf_counter()
+    tables, keep = resident_gradient_sets(w, n_sets, mode, few_dispatches)
     t_gen = time.perf_counter() - t_gen
 
     it = 0
@@ -107,6 +142,8 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
         pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
     torch.cuda.synchronize()
     _, st_bytes = algorithmic_bytes(w, pipe.cap, schedule, sgd is not None)
+    dominant = max(st_bytes, key=st_bytes.get)
+    iter_ms = []
     if graph:
         # every iteration replayed as one HIP graph (one graph per resident gradient set: the
         # tables are baked in); no events inside a graph, so no per-kernel times in this mode
@@ -123,32 +160,56 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
         t1 = time.perf_counter()
         probe = []
     else:
-        # events bracket only the dominant kernel unless a per-stage breakdown is asked for: every
-        # event is a packet between two kernels and costs a few microseconds of the step
-        pipe.probe, pipe.probe_only = [], (None if all_stages else max(st_bytes, key=st_bytes.get))
+        # inside the timed region: one event per iteration boundary, and events around the dominant
+        # stage only (every event is a packet between two kernels and costs a few microseconds)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        pipe.probe, pipe.probe_only = [], dominant
         t0 = time.perf_counter()
-        for _ in range(steps):
+        for i in range(steps):
+            marks[i].record()
             pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
+        marks[steps].record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         probe, pipe.probe = pipe.probe, None
+        iter_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
 
     ms_per_step = (t1 - t0) * 1e3 / steps
     L = int(pipe.packed_len.item()) if w.chunk else w.N
     total_bytes, per_stage_bytes = algorithmic_bytes(w, L, schedule, sgd is not None)
-    stage_ms = {}
-    for nm, e0, e1 in probe:
-        stage_ms.setdefault(nm, []).append(e0.elapsed_time(e1))
-    stage_avg = {nm: sum(v) / len(v) for nm, v in stage_ms.items()}
-    dominant = max(per_stage_bytes, key=per_stage_bytes.get)
+    dom_ms = [e0.elapsed_time(e1) for nm, e0, e1 in probe if nm == dominant]
+
+    # second pass, outside the timed region: every stage bracketed
+    stages = {}
+    if stage_pass and not graph:
+        pipe.probe, pipe.probe_only = [], None
+        for _ in range(min(steps, 10)):
+            pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
+        torch.cuda.synchronize()
+        probe2, pipe.probe = pipe.probe, None
+        per = {}
+        for nm, e0, e1 in probe2:
+            per.setdefault(nm, []).append(e0.elapsed_time(e1))
+        for nm, v in per.items():
+            med = statistics.median(v)
+            b = per_stage_bytes.get(nm, 0)
+            stages[nm] = {"median_ms": med, "min_ms": min(v), "bytes": b,
+                          "gbs": (b / med / 1e6) if b else None}
+
     res = {
         "workload": name, "P": w.P, "N": w.N, "m": w.m, "chunk": w.chunk, "k": pipe_k, "L": L,
         "schedule": schedule if w.chunk else "dense", "input": mode, "n_buckets": pipe.plan.n_buckets,
         "ms_per_step": ms_per_step, "bytes_per_step": total_bytes,
-        "gbs": total_bytes / ms_per_step / 1e6, "payload_gbs": w.P * w.N * (2 if w.grad == "f16" else 4) / ms_per_step / 1e6,
+        "median_ms": statistics.median(iter_ms) if iter_ms else None,
+        "min_ms": min(iter_ms) if iter_ms else None,
+        "gbs": total_bytes / ms_per_step / 1e6,
+        "payload_gbs": w.P * w.N * (2 if w.grad == "f16" else 4) / ms_per_step / 1e6,
         "elements_per_s": w.P * w.N / ms_per_step * 1e3,
-        "stage_ms": stage_avg, "stage_bytes": per_stage_bytes, "dominant": dominant,
-        "dominant_ms": stage_avg.get(dominant), "gen_s": t_gen, "steps_timed": steps,
+        "stage_bytes": per_stage_bytes, "dominant": dominant, "stages": stages,
+        "dominant_ms": (sum(dom_ms) / len(dom_ms)) if dom_ms else None,
+        "dominant_median_ms": statistics.median(dom_ms) if dom_ms else None,
+        "dominant_min_ms": min(dom_ms) if dom_ms else None,
+        "gen_s": t_gen, "steps_timed": steps,
     }
     del keep, tables, pipe
     torch.cuda.empty_cache()
@@ -201,23 +262,8 @@ def run_overlap(name: str, steps: int, warmup: int, n_streams: int = 2):
     return res
 
 
-def stream_probe():
-    """What bare kernels of the same access mixes sustain on this GPU (a stand-alone executable
-    that shares nothing with the library): context for the roofline fraction.  None if absent."""
-    import json as _json
-    import subprocess
-    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_1902_06855_amd", "probe", "stream_probe.bin")
-    if not os.path.exists(exe):
-        return None
-    try:
-        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
-        return _json.loads(r.stdout.strip().splitlines()[-1]) if r.returncode == 0 else None
-    except Exception:
-        return None
-
-
 def cpu_baseline(name: str, schedule: str, threads: int):
-    """The CPU checker, as it stands, on host cores: one whole steady-state iteration of the same
+    """The CPU checker, as it stands, on host cores: whole steady-state iterations of the same
     workload with the worker count cut down so that the run stays bounded.  Timed twice on the
     same inputs: with `threads` OpenMP threads (the reported value) and with one."""
     import numpy as np
@@ -270,25 +316,29 @@ def cpu_baseline(name: str, schedule: str, threads: int):
     }
 
 
+OTHER_KEYS = ("P", "N", "chunk", "k", "schedule", "n_buckets", "ms_per_step", "median_ms", "min_ms", "gbs",
+              "payload_gbs", "bytes_per_step", "stages", "dominant", "dominant_ms")
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="alexnet_csc")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--input", choices=["gather", "pool"], default="gather")
     ap.add_argument("--schedule", choices=["lagged", "immediate"], default="lagged")
-    ap.add_argument("--others", default="alexnet_dense,resnet50_dense_4mb,resnet50_dense_64mb,resnet50_csc",
+    ap.add_argument("--others", default=DEFAULT_OTHERS,
                     help="comma-separated extra workloads reported under config.others ('' = none)")
     ap.add_argument("--ladder", action="store_true",
                     help="also report the lower rungs of the ladder of Tables 1-2 (per-tensor fp32 / fp16 "
-                         "allreduce) and the fp16-input variants under config.others")
+                         "allreduce), the fp16-input, hierarchical-order, short-chunk and bucket-wise variants "
+                         "under config.others")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--stage-times", action="store_true", help="bracket every stage with events (adds a few us per step)")
-    ap.add_argument("--chunk", type=int, default=None, help="override the workload's chunk size (tuning aid)")
     ap.add_argument("--pmc-probe", action="store_true",
-                    help="for rocprofv3 --pmc runs: first a plain elementwise copy of known size (2 GiB read, "
-                         "2 GiB written) that calibrates the byte counters, then a short run of the workload")
+                    help="for the rocprofv3 --pmc commands recorded under profiles/: first a plain elementwise "
+                         "copy of known size (2 GiB read, 2 GiB written) that calibrates the byte counters, then 2 + 3 "
+                         "iterations of the workload on gradient sets drawn with one generator launch per worker")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the P workers are simulated in one GPU's HBM); "
@@ -301,7 +351,7 @@ def main() -> int:
     if a.ladder:
         a.others = ",".join([a.others] + list(wl.LADDER_NAMES))
     w = wl.config(a.workload)
-    steps = a.steps if a.steps is not None else max(10, w.iterations)
+    steps = a.steps if a.steps is not None else max(20, w.iterations)
     warmup = a.warmup if a.warmup is not None else 5
     n_sets = min(steps, 10) if w.chunk else 2
 
@@ -317,14 +367,14 @@ def main() -> int:
         torch.cuda.empty_cache()
         a.others, a.no_cpu_baseline = "", True
         steps, warmup, n_sets = 3, 2, 2
-    main_res = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk, a.stage_times)
+    main_res = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets,
+                       few_dispatches=a.pmc_probe, stage_pass=not a.pmc_probe)
     others = {}
     for nm in [x for x in a.others.split(",") if x and x != a.workload]:
         wo = wl.config(nm)
-        so = max(10, wo.iterations)
-        r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2, None, a.stage_times)
-        others[nm] = {kk: r[kk] for kk in ("P", "N", "schedule", "n_buckets", "ms_per_step", "gbs", "payload_gbs",
-                                            "stage_ms", "dominant", "dominant_ms")}
+        so = max(20, wo.iterations)
+        r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2)
+        others[nm] = {kk: r[kk] for kk in OTHER_KEYS}
         others[nm]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
         dom_b = r["stage_bytes"][r["dominant"]]
         others[nm]["dominant_gbs"] = dom_b / r["dominant_ms"] / 1e6
@@ -333,8 +383,8 @@ def main() -> int:
         # the same iterations replayed as HIP graphs (no events inside: whole-iteration time only)
         for nm in [a.workload] + [x for x in a.others.split(",") if x and x != a.workload and "dense" in x][:2]:
             wo = wl.config(nm)
-            so = max(10, wo.iterations)
-            r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2, None, False, None, True)
+            so = max(20, wo.iterations)
+            r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2, graph=True)
             others[nm + "+graph"] = {kk: r[kk] for kk in ("P", "N", "schedule", "ms_per_step", "gbs", "bytes_per_step")}
             others[nm + "+graph"]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
     if a.ladder and not a.pmc_probe:
@@ -342,9 +392,9 @@ def main() -> int:
             others[nm + "+buckets_on_side_streams"] = run_overlap(nm, 10, 5, 4)
     if w.chunk and not a.pmc_probe and a.others:
         # the same workload with Algorithm 1's SGD-update step fused into the unpack
-        r = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, a.chunk, a.stage_times, (0.9, -0.01))
+        r = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, sgd=(0.9, -0.01))
         others[a.workload + "+sgd_update"] = {kk: r[kk] for kk in ("P", "N", "schedule", "ms_per_step", "gbs",
-                                                                      "bytes_per_step", "stage_ms")}
+                                                                      "bytes_per_step", "stages")}
         others[a.workload + "+sgd_update"]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
     dom = main_res["dominant"]
     dom_bytes = main_res["stage_bytes"][dom]
@@ -355,23 +405,22 @@ def main() -> int:
     out = {
         "metric": "gradient GB/s per step (fuse+sparsify+reduce) and % of MI355X HBM peak",
         "value": main_res["gbs"], "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": main_res["ms_per_step"], "median_ms": main_res["median_ms"], "min_ms": main_res["min_ms"],
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32->f16" if w.wire == "f16" else "f32", "data": "synthetic",
         "frac_of_hbm_peak": main_res["gbs"] / HBM_PEAK_GBS,
         "payload_gbs": main_res["payload_gbs"], "elements_per_s": main_res["elements_per_s"],
         "config": {"workload": a.workload, "P": w.P, "N": w.N, "tensors": w.m, "chunk": w.chunk,
                    "k": main_res["k"], "packed_elems": main_res["L"], "loss_scale": w.loss_scale,
                    "schedule": main_res["schedule"], "input": a.input,
-                   "bytes_per_step": main_res["bytes_per_step"], "stage_ms": main_res["stage_ms"],
+                   "bytes_per_step": main_res["bytes_per_step"], "stages": main_res["stages"],
                    "gradient_sets_resident": n_sets, "others": others},
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "bytes_per_launch": dom_bytes,
-                     "avg_launch_ms": main_res["dominant_ms"],
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload)},
+                     "avg_launch_ms": main_res["dominant_ms"], "median_launch_ms": main_res["dominant_median_ms"],
+                     "min_launch_ms": main_res["dominant_min_ms"],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, a.input, main_res["schedule"]))},
     }
-    if not a.pmc_probe:
-        # a child process, run after the timed work (5 GB of its own buffers)
-        out["roofline"]["bare_kernel_reference"] = stream_probe()
     if not a.no_cpu_baseline:
         ncpu = min(16, os.cpu_count() or 1)
         out["cpu_baseline"] = cpu_baseline(a.workload, a.schedule, ncpu)

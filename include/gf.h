@@ -41,8 +41,9 @@ typedef enum {
     GF_ENOMEM = 2,   /* host or device allocation failed (plan calls only)          */
     GF_EHIP = 3,     /* a HIP runtime call or kernel launch failed                  */
     GF_ESTATE = 4,   /* plan in the wrong state: device tables missing (call
-                        gf_plan_to_device), or already uploaded for a setter that
-                        must run before                                             */
+                        gf_plan_to_device), already uploaded for a setter that
+                        must run before, or uploaded to another GPU than the one
+                        that is current at a compute call                           */
     GF_ELIMIT = 5    /* the plan needs more scratch than the fixed array of
                         gf_fuse_pack_static holds (use gf_fuse_pack)                */
 } gf_status;
@@ -104,7 +105,8 @@ gf_status gf_plan_set_grad_type(gf_plan *plan, gf_wire type);
 gf_status gf_plan_set_reduce_groups(gf_plan *plan, int32_t M);
 
 /* Copies the plan's tables to the current HIP device (allocates; synchronous).
- * Required once before any compute call; idempotent. */
+ * Required once before any compute call; idempotent.  Compute calls must be
+ * made with that same device current (GF_ESTATE otherwise). */
 gf_status gf_plan_to_device(gf_plan *plan);
 
 /* Frees host and device tables.  NULL is allowed. */

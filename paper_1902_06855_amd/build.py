@@ -9,8 +9,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgf.so")
-PROBE_SRC = os.path.join(HERE, "probe", "stream_probe.hip")
-PROBE = os.path.join(HERE, "probe", "stream_probe.bin")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -31,25 +29,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    extra = os.environ.get("GF_HIPCC_EXTRA", "").split()        # e.g. -DGF_FUSE_NT=512 -DGF_FUSE_U=8 when tuning
-    cmd = [hipcc] + HIPCC_FLAGS + extra + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB] + srcs
+    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB] + srcs
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
     return LIB
 
 
-def build_probe(verbose: bool = False) -> str:
-    """The stand-alone streaming probe (its own executable; shares nothing with the library)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-o", PROBE, PROBE_SRC]
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
-    return PROBE
-
-
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
-    print(build_probe(verbose=True))

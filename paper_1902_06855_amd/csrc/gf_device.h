@@ -30,26 +30,15 @@ typedef uint32_t gf_u32x4 __attribute__((ext_vector_type(4)));
 // Streaming accesses: data that is touched once per iteration bypasses the
 // caches (nontemporal), which on this part is worth several percent of HBM
 // bandwidth for mixed read/write streams.
-#ifndef GF_STREAM_NT
-#define GF_STREAM_NT 1
-#endif
 template <typename T>
 __device__ __forceinline__ T gf_ld_stream(const GF_GLOBAL T *p)
 {
-#if GF_STREAM_NT
     return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
 }
 template <typename T>
 __device__ __forceinline__ void gf_st_stream(T v, GF_GLOBAL T *p)
 {
-#if GF_STREAM_NT
     __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
 }
 
 // Buffer (resource-descriptor) accesses for the streaming kernels.  On this
@@ -58,9 +47,7 @@ __device__ __forceinline__ void gf_st_stream(T v, GF_GLOBAL T *p)
 // global_load/store ... nt (measured: in-place a += b at 6.5 vs 5.9 TB/s).  The
 // descriptor also bounds every access to the run it was made for: loads beyond
 // it return zero and stores are dropped.
-#ifndef GF_AUX_STREAM
-#define GF_AUX_STREAM 19            // sc0 | nt | sc1: touched once, keep it out of the caches
-#endif
+constexpr int GF_AUX_STREAM = 19;   // sc0 | nt | sc1: touched once, keep it out of the caches
 constexpr int GF_AUX_CACHED = 0;    // default policy: data that is read again soon
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t gf_make_buf(const GF_GLOBAL void *base, uint32_t bytes)

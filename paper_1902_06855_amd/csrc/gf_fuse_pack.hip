@@ -56,10 +56,8 @@ struct FuseArgs {
     float S, mu;
 };
 
-// 1: issue the first batch of historical-gradient loads before the gradients' address is known
-#ifndef GF_FUSE_PREFETCH
-#define GF_FUSE_PREFETCH 1
-#endif
+// issue the first batch of historical-gradient loads before the gradients' address is known
+constexpr bool FUSE_PREFETCH = true;
 
 template <int F, typename W>
 __device__ __forceinline__ void elem4(const gf_f32x4 g, const gf_f32x4 r, gf_f32x4 &res_out,
@@ -128,7 +126,7 @@ __device__ __forceinline__ bool run(Resolve &&resolve, float *res_, W *snd_, int
     const uint32_t run_bytes = static_cast<uint32_t>(len) * 4u;
     const __amdgpu_buffer_rsrc_t rb = gf_make_buf(res, ((F & F_RES) || WRITES_RES) ? run_bytes : 0u);
 
-    constexpr bool PREFETCH = GF_FUSE_PREFETCH && (F & F_RES) && (F & F_G);
+    constexpr bool PREFETCH = FUSE_PREFETCH && (F & F_RES) && (F & F_G);
     gf_f32x4 pre[U] = {};
     bool have_pre = PREFETCH && vec && U * NT <= (len >> 2);     // uniform: a whole first batch exists
     if constexpr (PREFETCH) {
@@ -427,22 +425,13 @@ gf_status launch_shape(const gf_plan *pl, FuseArgs a, int grp_shift, hipStream_t
 // pools, with the XCD-ordered work list): 256 threads that issue all 16 loads of
 // an 8192-element sub-tile before the first store, two workgroups resident per
 // SIMD set, runs of 32 sub-tiles (1 MB of a worker's pool) per XCD.
-#ifndef GF_FUSE_GRP_SHIFT
-#define GF_FUSE_GRP_SHIFT 5
-#endif
-#ifndef GF_DENSE_GRP_SHIFT
-#define GF_DENSE_GRP_SHIFT 5
-#endif
+constexpr int FUSE_GRP_SHIFT = 5, DENSE_GRP_SHIFT = 5;
 template <int MODE>
 gf_status launch(const gf_plan *pl, const FuseArgs &a, hipStream_t st)
 {
-#if defined(GF_FUSE_NT)
-    return launch_shape<MODE, GF_FUSE_NT, GF_FUSE_U, GF_FUSE_WPE>(pl, a, GF_FUSE_GRP_SHIFT, st);
-#else
-    if constexpr (MODE == MODE_DENSE) return launch_shape<MODE, 256, 8, 2>(pl, a, GF_DENSE_GRP_SHIFT, st);
-    if (a.sub <= 4096) return launch_shape<MODE, 256, 4, 2>(pl, a, GF_FUSE_GRP_SHIFT, st);
-    return launch_shape<MODE, 256, 8, 2>(pl, a, GF_FUSE_GRP_SHIFT, st);
-#endif
+    if constexpr (MODE == MODE_DENSE) return launch_shape<MODE, 256, 8, 2>(pl, a, DENSE_GRP_SHIFT, st);
+    if (a.sub <= 4096) return launch_shape<MODE, 256, 4, 2>(pl, a, FUSE_GRP_SHIFT, st);
+    return launch_shape<MODE, 256, 8, 2>(pl, a, FUSE_GRP_SHIFT, st);
 }
 
 }  // namespace
@@ -527,6 +516,7 @@ gf_status fuse_pack(const gf_plan *pl, uint32_t phase, const void *const *grads,
     const bool need_part = chunk_l1 && subs > 1;
     if ((need_map || need_part) && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return GF_EINVAL;
     if (!pl->on_device) return GF_ESTATE;
+    GF_CHECK_DEVICE(pl);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     FuseArgs a{};

@@ -13,17 +13,11 @@
 // Work tile of a dense-only plan, in pool elements.  Any multiple of 8 works;
 // 8192 elements = 32 KB of fp32 per worker per tile keeps >25k workgroups in
 // flight on the ResNet-50-sized pool while amortising the per-tile set-up.
-#ifndef GF_DENSE_TILE_ELEMS
-#define GF_DENSE_TILE_ELEMS 8192
-#endif
-constexpr int32_t GF_DENSE_TILE = GF_DENSE_TILE_ELEMS;
+constexpr int32_t GF_DENSE_TILE = 8192;
 
 // gf_fuse_pack cuts tiles longer than this into sub-tiles of this many elements
 // (a multiple of 4), one workgroup each.
-#ifndef GF_FUSE_SUB_ELEMS
-#define GF_FUSE_SUB_ELEMS 8192
-#endif
-constexpr int32_t GF_FUSE_SUB = GF_FUSE_SUB_ELEMS;
+constexpr int32_t GF_FUSE_SUB = 8192;
 
 // One contiguous run of a tensor inside a tile (pool order).
 struct gf_piece {
@@ -106,10 +100,7 @@ inline int64_t gf_csc_bucket_span(const gf_plan *p)
 // Threads per workgroup of the streaming kernels, and 16-byte groups each ring
 // workgroup covers.
 constexpr int GF_BLOCK = 256;
-#ifndef GF_RING_GPB
-#define GF_RING_GPB 512
-#endif
-constexpr int GF_RING_GROUPS_PER_BLOCK = GF_RING_GPB;   // = threads of a ring workgroup
+constexpr int GF_RING_GROUPS_PER_BLOCK = 512;   // = threads of a ring workgroup
 
 #define GF_HIP_TRY(expr)                        \
     do {                                        \
@@ -117,6 +108,14 @@ constexpr int GF_RING_GROUPS_PER_BLOCK = GF_RING_GPB;   // = threads of a ring w
             (void)hipGetLastError();            \
             return GF_EHIP;                     \
         }                                       \
+    } while (0)
+
+// Compute calls run on the device the plan's tables were uploaded to.
+#define GF_CHECK_DEVICE(pl)                                         \
+    do {                                                            \
+        int cur_ = -1;                                              \
+        GF_HIP_TRY(hipGetDevice(&cur_));                            \
+        if (cur_ != (pl)->device) return GF_ESTATE;                 \
     } while (0)
 
 #define GF_LAUNCH_CHECK()                       \

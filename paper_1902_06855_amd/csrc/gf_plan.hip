@@ -15,7 +15,7 @@ extern "C" const char *gf_status_string(gf_status s)
     case GF_EINVAL: return "GF_EINVAL: invalid argument";
     case GF_ENOMEM: return "GF_ENOMEM: allocation failed";
     case GF_EHIP: return "GF_EHIP: HIP runtime error";
-    case GF_ESTATE: return "GF_ESTATE: plan in the wrong state (tables not on the device, or already uploaded)";
+    case GF_ESTATE: return "GF_ESTATE: plan in the wrong state (tables not on the device, already uploaded, or on another device)";
     case GF_ELIMIT: return "GF_ELIMIT: the plan needs more scratch than gf_fuse_pack_static's fixed array holds";
     }
     return "unknown gf_status";

@@ -20,9 +20,7 @@
 namespace {
 
 // log2 of the consecutive workgroups (8 KB of every send buffer each) one XCD takes
-#ifndef GF_RING_GRP_SHIFT
-#define GF_RING_GRP_SHIFT 5
-#endif
+constexpr int RING_GRP_SHIFT = 5;
 
 // A dense plan's send buffers (P * N wire elements) are far larger than the
 // caches and are read exactly once: they are streamed.  The packed buffer of a
@@ -89,7 +87,7 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
     const int M = HIER ? a.M : P;     // segments per bucket
     int64_t lo, hi, seg;
     int s, bis;
-    const uint32_t item = gf_xcd_order(blockIdx.x, gridDim.x, GF_RING_GRP_SHIFT);
+    const uint32_t item = gf_xcd_order(blockIdx.x, gridDim.x, RING_GRP_SHIFT);
     if constexpr (DENSE) {
         const gf_ring_block rb = a.blocks[item];
         const gf_bucket_dev bk = a.buckets[rb.bucket];
@@ -227,6 +225,7 @@ extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *se
     if (dense && (L != pl->N || L_dev)) return GF_EINVAL;
     if (!dense && L > static_cast<int64_t>(pl->n_chunks) * pl->chunk) return GF_EINVAL;
     if (!pl->on_device) return GF_ESTATE;
+    GF_CHECK_DEVICE(pl);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     RingArgs a{};

@@ -170,6 +170,7 @@ extern "C" gf_status gf_chunk_score_select(const gf_plan *pl, const float *chunk
         scores = reinterpret_cast<float *>(static_cast<char *>(workspace) + gf_ws_scores_off(pl));
     }
     if (!pl->on_device) return GF_ESTATE;
+    GF_CHECK_DEVICE(pl);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int32_t nc = pl->n_chunks;
 

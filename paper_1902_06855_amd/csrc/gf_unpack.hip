@@ -26,9 +26,7 @@ struct UnpackArgs {
 };
 
 // log2 of the consecutive tiles one XCD takes
-#ifndef GF_UNPACK_GRP_SHIFT
-#define GF_UNPACK_GRP_SHIFT 4
-#endif
+constexpr int UNPACK_GRP_SHIFT = 4;
 
 // One contiguous run.  dst may be null in the update variant (gradient not kept).
 template <typename W, bool UPD, int NT>
@@ -123,7 +121,7 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
 template <typename W, bool UPD, int NT>
 __global__ __launch_bounds__(NT) void k_unpack(const UnpackArgs a)
 {
-    const int j = gf_xcd_order(blockIdx.x, gridDim.x, GF_UNPACK_GRP_SHIFT);
+    const int j = gf_xcd_order(blockIdx.x, gridDim.x, UNPACK_GRP_SHIFT);
     const int tile = a.sel_idx ? a.sel_idx[j] : j;
     const int64_t tile_lo = static_cast<int64_t>(tile) * a.tile;
     const int64_t left = a.N - tile_lo;
@@ -185,6 +183,7 @@ gf_status unpack_common(const gf_plan *pl, UnpackArgs &a, int64_t L, int32_t k, 
         blocks = pl->n_tiles;
     }
     if (!pl->on_device) return GF_ESTATE;
+    GF_CHECK_DEVICE(pl);
     a.piece_start = pl->d_piece_start;
     a.pieces = pl->d_pieces;
     a.N = pl->N;

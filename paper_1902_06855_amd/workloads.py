@@ -136,6 +136,17 @@ def config(name: str) -> Workload:
         w = config("alexnet_dense")
         w.name, w.extra = name, {"groups": 2}
         return w
+    if name.endswith("_p1") and name[:-3] in ("alexnet_csc", "resnet50_csc"):
+        # one worker: the shape each GPU of a real job runs (its own gradients, its own historical
+        # gradient; the exchange itself is the network's and degenerates to a copy here)
+        w = config(name[:-3])
+        w.name, w.P = name, 1
+        return w
+    for c in (2048, 4096):                     # the ResNet-50 set cut into short chunks
+        if name == f"resnet50_csc_c{c}":
+            w = config("resnet50_csc")
+            w.name, w.chunk, w.P = name, c, 16
+            return w
     if name == "alexnet_csc_fp16in":           # sparse path fed with fp16 gradients
         w = config("alexnet_csc")
         w.name, w.grad = name, "f16"
@@ -145,7 +156,8 @@ def config(name: str) -> Workload:
 
 LADDER_NAMES = ("alexnet_pertensor_fp32", "alexnet_pertensor_fp16", "alexnet_fp16pool", "alexnet_csc_fp16in",
                 "resnet50_pertensor_fp32", "resnet50_pertensor_fp16", "resnet50_fp16pool",
-                "alexnet_dense_hier", "alexnet_csc_hier", "resnet50_csc_hier")
+                "alexnet_dense_hier", "alexnet_csc_hier", "resnet50_csc_hier",
+                "resnet50_csc_c4096", "resnet50_csc_c2048")
 
 CONFIG_NAMES = ("tiny", "alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb",
                 "alexnet_csc", "resnet50_csc")
@@ -172,6 +184,11 @@ def _mix(*vals: int) -> int:
         x = (x * 0x94D049BB133111EB) & 0xFFFFFFFFFFFFFFFF
         x ^= x >> 29
     return x & 0x7FFFFFFFFFFFFFFF
+
+
+def stream_seed(*vals: int) -> int:
+    """Seed of an independent random stream named by a tuple of small integers."""
+    return _mix(*vals)
 
 
 def sigma_table(w: Workload) -> np.ndarray:
