@@ -58,6 +58,11 @@ typedef void *gf_stream;             /* hipStream_t */
 /* phase bits of gf_fuse_pack */
 #define GF_PHASE_ACCUM 1u            /* g + hg, chunk norms                        */
 #define GF_PHASE_PACK  2u            /* cast, scale, pack, historical-gradient rule */
+/* modifiers, for callers that run the four calls back to back on one workspace   */
+#define GF_PHASE_SLOTS 4u            /* the workspace already holds the slot map of
+                                        sel_idx (gf_chunk_score_select left it)    */
+#define GF_PHASE_DEFER_NORMS 8u      /* leave the chunk norms in the workspace for
+                                        gf_chunk_score_select to finish            */
 
 const char *gf_status_string(gf_status s);
 
@@ -135,7 +140,13 @@ int32_t gf_plan_tile_pieces(const gf_plan *plan, int32_t tile, int32_t cap,
                             int32_t *tensor, int64_t *src_off, int32_t *len);
 
 /* Bytes of device scratch the compute calls need (pass it as `workspace`,
- * 256-byte aligned; its contents carry nothing between calls). */
+ * 256-byte aligned).  Its contents carry nothing from one call to the next,
+ * except for the two hand-overs a caller may ask for explicitly: the slot map
+ * that gf_chunk_score_select leaves for gf_fuse_pack (GF_PHASE_SLOTS) and the
+ * unfinished chunk norms that gf_fuse_pack leaves for gf_chunk_score_select
+ * (GF_PHASE_DEFER_NORMS).  Calls that may run at the same time must not share a
+ * workspace, except gf_fuse_pack_range calls over disjoint chunk ranges that
+ * all pass GF_PHASE_SLOTS. */
 size_t gf_plan_workspace_bytes(const gf_plan *plan);
 
 /* Warm-up dense training (Section 3.2): over the first `warmup_iterations`
@@ -182,9 +193,22 @@ int32_t gf_plan_warmup_k(const gf_plan *plan, double final_density, int64_t iter
  *                        already known: the paper's schedule, or the dense path).
  * mu is Algorithm 1's "momentum" applied to the historical gradient.
  * workspace (gf_plan_workspace_bytes, 256-byte aligned) is needed when sel_idx
- * is given together with GF_PHASE_PACK, and when chunk_l1 is asked for on a plan
+ * is given together with GF_PHASE_PACK, when chunk_l1 is asked for on a plan
  * whose chunks are longer than 8192 elements (partial norms are combined
- * there); GF_EINVAL if it is missing then.  It may be NULL otherwise. */
+ * there), and with either modifier bit; GF_EINVAL if it is missing then.  It may
+ * be NULL otherwise.
+ *
+ * Modifier bits (Section 3.2: the important chunks of an iteration are chosen
+ * at the end of the one before, so a steady-state iteration is this call, the
+ * allreduce, the unpack and the selection, back to back on one workspace):
+ *   GF_PHASE_SLOTS        with sel_idx and GF_PHASE_PACK: sel_idx / k are the
+ *     selection the last gf_chunk_score_select on this workspace produced and
+ *     nothing has written the workspace's slot map since; the call then does
+ *     not rebuild it (one small launch fewer).
+ *   GF_PHASE_DEFER_NORMS  with GF_PHASE_ACCUM on a CSC plan: the chunk norms
+ *     stay in the workspace as per-sub-tile partial sums, chunk_l1 is ignored
+ *     (may be NULL), and the next gf_chunk_score_select on this workspace, called
+ *     with chunk_l1 NULL, finishes them (same values, same order of additions). */
 gf_status gf_fuse_pack(const gf_plan *plan, uint32_t phase,
                        const void *const *grads, const float *const *pools,
                        float *const *residual,
@@ -192,6 +216,29 @@ gf_status gf_fuse_pack(const gf_plan *plan, uint32_t phase,
                        float loss_scale, float mu,
                        void *const *sendbuf, float *chunk_l1,
                        void *workspace, gf_stream stream);
+
+/* --------------------------------------------------------- gf_fuse_pack_range
+ * gf_fuse_pack over the chunks [chunk_lo, chunk_hi) only, for a caller that
+ * packs the important chunks while backward is still filling the pool
+ * (Section 3.2: "if an important chunk is filled, CSC copies its data to a
+ * buffer; when the buffer size is greater than a given threshold, CSC starts
+ * an allreduce"; Section 3.1, enable-overlap setting): once the gradients of
+ * pool elements [chunk_lo * C, min(N, chunk_hi * C)) exist, this call does for
+ * those chunks exactly what gf_fuse_pack does for all of them -- sel_idx / k
+ * are still the whole selection, the j-th selected chunk still lands at
+ * element j*C of the send buffers, chunk_l1 entries outside the range are not
+ * touched -- so that calls over ranges that tile [0, n_chunks) leave the same
+ * bytes everywhere as one gf_fuse_pack.  CSC plans only; phase must include
+ * GF_PHASE_ACCUM; 0 <= chunk_lo <= chunk_hi <= n_chunks (an empty range does
+ * nothing).  Without GF_PHASE_SLOTS every call rebuilds the whole slot map. */
+gf_status gf_fuse_pack_range(const gf_plan *plan, uint32_t phase,
+                             const void *const *grads, const float *const *pools,
+                             float *const *residual,
+                             const int32_t *sel_idx, int32_t k,
+                             float loss_scale, float mu,
+                             void *const *sendbuf, float *chunk_l1,
+                             int32_t chunk_lo, int32_t chunk_hi,
+                             void *workspace, gf_stream stream);
 
 /* -------------------------------------------------------- gf_fuse_pack_static
  * gf_fuse_pack for callers that can neither allocate device memory nor hand a
@@ -202,7 +249,8 @@ gf_status gf_fuse_pack(const gf_plan *plan, uint32_t phase,
  * (every GPU the library runs on holds one copy until the process ends).  The
  * call allocates nothing and frees nothing.
  * GF_ELIMIT if gf_plan_workspace_bytes(plan) > GF_STATIC_SCRATCH_BYTES (nothing
- * is launched); other errors as gf_fuse_pack.  All calls on one GPU share that
+ * is launched); GF_EINVAL for the two modifier bits (the array is private to
+ * this entry point); other errors as gf_fuse_pack.  All calls on one GPU share that
  * GPU's array, which keeps the previous call's contents (every entry a call
  * reads is written by that call first): two calls that overlap in time on one
  * GPU, on different streams or from different threads, race. */
@@ -232,6 +280,11 @@ gf_status gf_fuse_pack_static(const gf_plan *plan, uint32_t phase,
  *   mask [n_chunks] bytes (1 = chosen), packed_len [1] int64 (number of
  *   elements the chosen chunks hold): device, out; scores, mask and
  *   packed_len may be NULL.  sel_idx may be the same buffer as prev_sel.
+ * chunk_l1 NULL: the norms are those the last gf_fuse_pack on this workspace
+ *   left there (GF_PHASE_DEFER_NORMS).
+ * workspace: needed when scores or chunk_l1 is NULL.  Whenever it is given the
+ *   call also leaves the slot map of the new selection in it (rank of every
+ *   chosen chunk, -1 elsewhere) for a gf_fuse_pack with GF_PHASE_SLOTS.
  * 1 <= k <= n_chunks.  CSC plans only. */
 gf_status gf_chunk_score_select(const gf_plan *plan, const float *chunk_l1,
                                 const float *reduced_l1, const int32_t *prev_sel, int32_t k_prev,
@@ -267,6 +320,24 @@ gf_status gf_ring_reduce_sim(const gf_plan *plan, const void *const *sendbuf, in
                              const int64_t *L_dev, void *reduced, void *const *allgather_out,
                              void *workspace, gf_stream stream);
 
+/* ------------------------------------------------------- gf_ring_reduce_range
+ * gf_ring_reduce_sim for a CSC plan whose packed buffer is filled range by
+ * range (gf_fuse_pack_range) while backward is still running: reduces exactly
+ * those lazy-allreduce buckets of the packed buffer whose last chunk lies in
+ * [chunk_lo, chunk_hi) -- the buckets that the sweep over that range completed
+ * (Section 3.2: the allreduce of a bucket starts once the buffer holds more
+ * than theta).  Which buckets those are is decided on the device from sel_idx
+ * (the selection the buffer was packed with, k entries); the host needs no
+ * copy of it, so a whole iteration can be recorded in a graph.  Calls over
+ * ranges that tile [0, n_chunks) together leave the same bytes in `reduced`
+ * as one gf_ring_reduce_sim.  L must be k * C (the buffer's capacity); L_dev as
+ * in gf_ring_reduce_sim.  The caller orders the call after the gf_fuse_pack_range
+ * calls of this and all earlier ranges. */
+gf_status gf_ring_reduce_range(const gf_plan *plan, const void *const *sendbuf, int64_t L,
+                               const int64_t *L_dev, const int32_t *sel_idx, int32_t k,
+                               int32_t chunk_lo, int32_t chunk_hi, void *reduced,
+                               void *const *allgather_out, void *workspace, gf_stream stream);
+
 /* ------------------------------------------------------------ gf_unpack_apply
  * Second cast of Section 2.5 and the write-back of Section 3.2:
  *     out[c*C + i] = fp32(reduced[j*C + i]) * alpha     for c = sel_idx[j]
@@ -281,6 +352,16 @@ gf_status gf_ring_reduce_sim(const gf_plan *plan, const void *const *sendbuf, in
 gf_status gf_unpack_apply(const gf_plan *plan, const void *reduced, int64_t L,
                           const int32_t *sel_idx, int32_t k, float alpha,
                           float *out_pool, void *const *out_tensors,
+                          float *reduced_l1, void *workspace, gf_stream stream);
+
+/* ------------------------------------------------------------ gf_unpack_range
+ * gf_unpack_apply for the chunks of the packed buckets that
+ * gf_ring_reduce_range reduces for the same [chunk_lo, chunk_hi): the other
+ * selected chunks (and their reduced_l1 entries) are left for the calls whose
+ * range completes their bucket.  Other arguments as in gf_unpack_apply. */
+gf_status gf_unpack_range(const gf_plan *plan, const void *reduced, int64_t L,
+                          const int32_t *sel_idx, int32_t k, int32_t chunk_lo, int32_t chunk_hi,
+                          float alpha, float *out_pool, void *const *out_tensors,
                           float *reduced_l1, void *workspace, gf_stream stream);
 
 /* ------------------------------------------------------- gf_unpack_sgd_update

@@ -124,3 +124,74 @@ def csc_iteration(state: CscState, pools: np.ndarray, C: int, k: int, S: float, 
         state.sel = nxt
         r["score_post"], r["sel_next"] = sc, nxt
     return r
+
+
+def csc_iteration_in_ranges(state: CscState, pools: np.ndarray, C: int, k: int, S: float, mu: float,
+                            boundaries: Sequence[int], theta: int, wire: str = "f16",
+                            out: Optional[np.ndarray] = None, k_next: Optional[int] = None,
+                            groups: int = 0) -> Dict[str, np.ndarray]:
+    """A steady-state iteration of the lagged schedule the way Section 3.2 describes it running
+    while backward is still filling the pool (the enable-overlap setting of Section 3.1).
+
+    The pool fills in generation order, that is by ascending chunk index.  `boundaries` are
+    ascending chunk indices ending with n_chunks: the pool is swept range by range,
+    [0, b_0), [b_0, b_1), ...  A sweep accumulates, takes the norms of and packs the chunks of its
+    range only (an important chunk that is filled is copied to the buffer).  After each sweep
+    every bucket of the packed buffer that has just become complete (the waiting chunks exceed
+    theta, or the pool's last important chunk is in) is allreduced and unpacked.  Selection
+    follows once the pool is done.  Nothing here depends on how the pool is cut into ranges, so
+    the result must equal csc_iteration(theta=theta) bit for bit; the tests check that.
+    """
+    assert state.sel is not None, "the first iteration chooses from its own gradients: nothing to overlap"
+    P, N = pools.shape
+    nc = ob.n_chunks(N, C)
+    bounds = [int(b) for b in boundaries]
+    assert bounds == sorted(set(bounds)) and bounds[-1] == nc and bounds[0] > 0
+    sel = state.sel
+    L = ob.packed_len(N, C, sel)
+    wdt = ob.WIRE_DTYPE[wire]
+    send = np.zeros((P, L), dtype=wdt)
+    reduced = np.zeros(L, dtype=wdt)
+    hg = state.hg.copy()
+    acc = np.empty_like(pools)
+    l1 = np.empty((P, nc), dtype=np.float32)
+    if out is None:
+        out = np.zeros(N, dtype=np.float32)
+    red_l1 = np.zeros(len(sel), dtype=np.float32)
+    slot_of = {int(c): j for j, c in enumerate(sel)}           # rank of a chunk in the selection
+    slot_start = np.concatenate([[0], np.cumsum([min(N, (int(c) + 1) * C) - int(c) * C for c in sel])])
+    b_lo, b_hi = ob.packed_buckets(N, C, sel, theta)
+    # chunks (by rank in the selection) of every packed bucket
+    members = [[j for j in range(len(sel)) if a <= slot_start[j] < b] for a, b in zip(b_lo, b_hi)]
+    packed = np.zeros(len(sel), dtype=bool)
+    done = np.zeros(len(b_lo), dtype=bool)
+    alpha = np.float32(1.0) / np.float32(S)
+    lo = 0
+    for hi in bounds:
+        e_lo, e_hi = lo * C, min(N, hi * C)
+        a_r = ob.accumulate(np.ascontiguousarray(pools[:, e_lo:e_hi]), np.ascontiguousarray(hg[:, e_lo:e_hi]))
+        acc[:, e_lo:e_hi] = a_r
+        l1[:, lo:hi] = ob.chunk_l1(a_r, C)
+        mine = np.array([c - lo for c in sel if lo <= c < hi], dtype=np.int32)
+        s_r, hg_r = ob.pack_residual(a_r, C, mine, S, mu, wire)
+        hg[:, e_lo:e_hi] = hg_r
+        if len(mine):
+            j0 = slot_of[int(mine[0]) + lo]
+            send[:, slot_start[j0]:slot_start[j0] + s_r.shape[1]] = s_r
+            packed[j0:j0 + len(mine)] = True
+        for b, mem in enumerate(members):                       # buckets this sweep completed
+            if done[b] or not (lo <= sel[mem[-1]] < hi):
+                continue
+            assert packed[mem].all(), "a bucket is reduced only when all its chunks are in the buffer"
+            a, e = int(b_lo[b]), int(b_hi[b])
+            reduced[a:e] = ob.allreduce(np.ascontiguousarray(send[:, a:e]), wire, groups)
+            red_l1[mem] = ob.unpack(reduced[a:e], N, C, sel[mem], alpha, out, wire)
+            done[b] = True
+        lo = hi
+    assert done.all() and packed.all()
+    state.hg = hg
+    sc = ob.score(l1, sel, red_l1)
+    nxt, _ = ob.select(sc, k if k_next is None else k_next)
+    state.sel = nxt
+    return dict(acc=acc, l1=l1, sel=sel, send=send, hg=hg, reduced=reduced, out=out, red_l1=red_l1,
+                score_post=sc, sel_next=nxt, packed_bucket_lo=b_lo, packed_bucket_hi=b_hi)

@@ -50,6 +50,7 @@ struct FuseArgs {
     double *l1_part;             // [P * n_tiles * subs] partial norms when subs > 1
     int64_t N;
     int32_t tile, n_tiles, units; // units: tiles to visit per worker
+    int32_t tile_first;           // first tile of the visited range (0 unless a chunk range was asked for)
     int32_t sub, subs;            // sub-tile length (elements) and sub-tiles per tile
     uint32_t total;               // workgroups = P * units * subs
     int32_t grp_shift;            // log2 of the consecutive work items one XCD takes
@@ -321,10 +322,10 @@ void k_fuse(const FuseArgs a)
     const uint32_t r = item - p * per_worker;
     const int u = a.subs == 1 ? r : r / a.subs;
     const int sub = a.subs == 1 ? 0 : r - u * a.subs;
-    int tile = u;
-    int64_t slot = u;
+    int tile = a.tile_first + u;
+    int64_t slot = tile;
     if constexpr (MODE == MODE_PACK) {
-        if (a.sel_idx) tile = a.sel_idx[u];
+        if (a.sel_idx) { tile = a.sel_idx[u]; slot = u; }
     }
     // One round of table look-ups, issued together.  Unused entries read a valid dummy
     // location instead of branching, so that none of them waits for another.
@@ -362,22 +363,26 @@ void k_fuse(const FuseArgs a)
     }
     if constexpr (MODE == MODE_ACCUM || MODE == MODE_FUSED) {
         const double s = gf_block_sum<NT>(l1);
-        if (a.chunk_l1 && threadIdx.x == 0) {
+        if (threadIdx.x == 0) {
             const int64_t c = static_cast<int64_t>(p) * a.n_tiles + tile;
-            if (a.subs == 1) a.chunk_l1[c] = static_cast<float>(s);
-            else a.l1_part[c * a.subs + sub] = s;
+            if (a.l1_part) a.l1_part[c * a.subs + sub] = s;          // finished later, in a fixed order
+            else if (a.chunk_l1) a.chunk_l1[c] = static_cast<float>(s);
         }
     }
 }
 
-// chunk_l1[c] = sum of the chunk's sub-tile norms, first sub-tile first (fp64), rounded once.
-__global__ __launch_bounds__(GF_BLOCK) void k_l1_combine(const double *__restrict__ part, int64_t n, int32_t subs,
+// chunk_l1[c] = sum of the chunk's sub-tile norms, first sub-tile first (fp64), rounded once,
+// for chunks [first, first + count) of every worker.
+__global__ __launch_bounds__(GF_BLOCK) void k_l1_combine(const double *__restrict__ part, int32_t P, int32_t n_tiles,
+                                                         int32_t first, int32_t count, int32_t subs,
                                                          float *__restrict__ chunk_l1)
 {
-    const int64_t c = static_cast<int64_t>(blockIdx.x) * GF_BLOCK + threadIdx.x;
-    if (c >= n) return;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * GF_BLOCK + threadIdx.x;
+    if (i >= static_cast<int64_t>(P) * count) return;
+    const int64_t p = i / count;
+    const int64_t c = p * n_tiles + first + (i - p * count);
     double s = part[c * subs];
-    for (int i = 1; i < subs; ++i) s += part[c * subs + i];
+    for (int j = 1; j < subs; ++j) s += part[c * subs + j];
     chunk_l1[c] = static_cast<float>(s);
 }
 
@@ -464,56 +469,31 @@ gf_status static_scratch(void **out)
     return GF_OK;
 }
 
+// Chunks [chunk_lo, chunk_hi) of every worker (the whole pool for a dense plan).
 gf_status fuse_pack(const gf_plan *pl, uint32_t phase, const void *const *grads, const float *const *pools,
                     float *const *residual, const int32_t *sel_idx, int32_t k, float loss_scale, float mu,
-                    void *const *sendbuf, float *chunk_l1, void *workspace, gf_stream stream);
-
-}  // namespace
-
-extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
-                                  const void *const *grads, const float *const *pools,
-                                  float *const *residual,
-                                  const int32_t *sel_idx, int32_t k,
-                                  float loss_scale, float mu,
-                                  void *const *sendbuf, float *chunk_l1,
-                                  void *workspace, gf_stream stream)
-{
-    return fuse_pack(pl, phase, grads, pools, residual, sel_idx, k, loss_scale, mu, sendbuf, chunk_l1, workspace, stream);
-}
-
-extern "C" gf_status gf_fuse_pack_static(const gf_plan *pl, uint32_t phase,
-                                         const void *const *grads, const float *const *pools,
-                                         float *const *residual,
-                                         const int32_t *sel_idx, int32_t k,
-                                         float loss_scale, float mu,
-                                         void *const *sendbuf, float *chunk_l1, gf_stream stream)
+                    void *const *sendbuf, float *chunk_l1, int32_t chunk_lo, int32_t chunk_hi,
+                    void *workspace, gf_stream stream)
 {
     if (!pl) return GF_EINVAL;
-    if (gf_ws_total_bytes(pl) > static_cast<size_t>(GF_STATIC_SCRATCH_BYTES)) return GF_ELIMIT;
-    void *ws = nullptr;
-    const gf_status rc = static_scratch(&ws);
-    if (rc != GF_OK) return rc;
-    return fuse_pack(pl, phase, grads, pools, residual, sel_idx, k, loss_scale, mu, sendbuf, chunk_l1, ws, stream);
-}
-
-namespace {
-
-gf_status fuse_pack(const gf_plan *pl, uint32_t phase, const void *const *grads, const float *const *pools,
-                    float *const *residual, const int32_t *sel_idx, int32_t k, float loss_scale, float mu,
-                    void *const *sendbuf, float *chunk_l1, void *workspace, gf_stream stream)
-{
-    if (!pl) return GF_EINVAL;
-    if (phase == 0 || (phase & ~(GF_PHASE_ACCUM | GF_PHASE_PACK))) return GF_EINVAL;
+    constexpr uint32_t KNOWN = GF_PHASE_ACCUM | GF_PHASE_PACK | GF_PHASE_SLOTS | GF_PHASE_DEFER_NORMS;
+    if ((phase & (GF_PHASE_ACCUM | GF_PHASE_PACK)) == 0 || (phase & ~KNOWN)) return GF_EINVAL;
     const bool accum = phase & GF_PHASE_ACCUM, pack = phase & GF_PHASE_PACK;
+    const bool slots_ready = phase & GF_PHASE_SLOTS, defer = phase & GF_PHASE_DEFER_NORMS;
     if (accum && ((grads != nullptr) == (pools != nullptr))) return GF_EINVAL;
     if (pack && !sendbuf) return GF_EINVAL;
     if (!residual && (!(accum && pack) || sel_idx || chunk_l1)) return GF_EINVAL;
-    if ((sel_idx || chunk_l1) && pl->chunk == 0) return GF_EINVAL;
-    if (chunk_l1 && !accum) return GF_EINVAL;
+    if ((sel_idx || chunk_l1 || defer) && pl->chunk == 0) return GF_EINVAL;
+    if ((chunk_l1 || defer) && !accum) return GF_EINVAL;
+    if (defer && !residual) return GF_EINVAL;
     if (sel_idx && pack && (k < 1 || k > pl->n_chunks)) return GF_EINVAL;
+    if (slots_ready && !(sel_idx && pack)) return GF_EINVAL;
+    if (chunk_lo < 0 || chunk_hi > pl->n_tiles || chunk_lo > chunk_hi) return GF_EINVAL;
+    const bool whole = chunk_lo == 0 && chunk_hi == pl->n_tiles;
+    if (!whole && (pl->chunk == 0 || !accum)) return GF_EINVAL;      // a range needs chunks and the gradient pass
     const bool need_map = sel_idx && pack && (accum || mu != 1.0f);
     const int32_t subs = gf_fuse_subs(pl);
-    const bool need_part = chunk_l1 && subs > 1;
+    const bool need_part = defer || (chunk_l1 && subs > 1);
     if ((need_map || need_part) && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))) return GF_EINVAL;
     if (!pl->on_device) return GF_ESTATE;
     GF_CHECK_DEVICE(pl);
@@ -525,24 +505,26 @@ gf_status fuse_pack(const gf_plan *pl, uint32_t phase, const void *const *grads,
     a.use_pieces = grads ? 1 : 0;
     a.residual = residual;
     a.sendbuf = sendbuf;
-    a.chunk_l1 = chunk_l1;
+    a.chunk_l1 = defer ? nullptr : chunk_l1;
     a.piece_start = pl->d_piece_start;
     a.pieces = pl->d_pieces;
     a.unit_src = pl->d_unit_src;
     a.N = pl->N;
     a.tile = pl->tile;
     a.n_tiles = pl->n_tiles;
-    a.units = pl->n_tiles;
+    a.tile_first = chunk_lo;
+    a.units = chunk_hi - chunk_lo;
     a.sub = gf_fuse_sub_len(pl);
     a.subs = subs;
     if (need_part) a.l1_part = reinterpret_cast<double *>(static_cast<char *>(workspace) + gf_ws_l1part_off(pl));
     a.S = loss_scale;
     a.mu = mu;
-    const int64_t n_norms = static_cast<int64_t>(pl->P) * pl->n_tiles;
+    if (a.units == 0) return GF_OK;
     auto combine = [&](gf_status rc) {
-        if (rc != GF_OK || !need_part) return rc;
+        if (rc != GF_OK || defer || !(chunk_l1 && subs > 1)) return rc;
+        const int64_t n_norms = static_cast<int64_t>(pl->P) * a.units;
         hipLaunchKernelGGL(k_l1_combine, dim3(static_cast<unsigned>((n_norms + GF_BLOCK - 1) / GF_BLOCK)), dim3(GF_BLOCK),
-                           0, st, a.l1_part, n_norms, subs, chunk_l1);
+                           0, st, a.l1_part, pl->P, pl->n_tiles, chunk_lo, a.units, subs, chunk_l1);
         GF_LAUNCH_CHECK();
         return GF_OK;
     };
@@ -550,9 +532,11 @@ gf_status fuse_pack(const gf_plan *pl, uint32_t phase, const void *const *grads,
     int32_t *slotmap = nullptr;
     if (need_map) {
         slotmap = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + gf_ws_slotmap_off());
-        hipLaunchKernelGGL(k_slotmap, dim3((pl->n_chunks + GF_BLOCK - 1) / GF_BLOCK), dim3(GF_BLOCK), 0, st,
-                           sel_idx, k, pl->n_chunks, slotmap);
-        GF_LAUNCH_CHECK();
+        if (!slots_ready) {
+            hipLaunchKernelGGL(k_slotmap, dim3((pl->n_chunks + GF_BLOCK - 1) / GF_BLOCK), dim3(GF_BLOCK), 0, st,
+                               sel_idx, k, pl->n_chunks, slotmap);
+            GF_LAUNCH_CHECK();
+        }
     }
 
     if (accum && !pack) {
@@ -575,3 +559,48 @@ gf_status fuse_pack(const gf_plan *pl, uint32_t phase, const void *const *grads,
 }
 
 }  // namespace
+
+extern "C" gf_status gf_fuse_pack(const gf_plan *pl, uint32_t phase,
+                                  const void *const *grads, const float *const *pools,
+                                  float *const *residual,
+                                  const int32_t *sel_idx, int32_t k,
+                                  float loss_scale, float mu,
+                                  void *const *sendbuf, float *chunk_l1,
+                                  void *workspace, gf_stream stream)
+{
+    if (!pl) return GF_EINVAL;
+    return fuse_pack(pl, phase, grads, pools, residual, sel_idx, k, loss_scale, mu, sendbuf, chunk_l1,
+                     0, pl->n_tiles, workspace, stream);
+}
+
+extern "C" gf_status gf_fuse_pack_range(const gf_plan *pl, uint32_t phase,
+                                        const void *const *grads, const float *const *pools,
+                                        float *const *residual,
+                                        const int32_t *sel_idx, int32_t k,
+                                        float loss_scale, float mu,
+                                        void *const *sendbuf, float *chunk_l1,
+                                        int32_t chunk_lo, int32_t chunk_hi,
+                                        void *workspace, gf_stream stream)
+{
+    if (!pl || pl->chunk == 0) return GF_EINVAL;
+    return fuse_pack(pl, phase, grads, pools, residual, sel_idx, k, loss_scale, mu, sendbuf, chunk_l1,
+                     chunk_lo, chunk_hi, workspace, stream);
+}
+
+extern "C" gf_status gf_fuse_pack_static(const gf_plan *pl, uint32_t phase,
+                                         const void *const *grads, const float *const *pools,
+                                         float *const *residual,
+                                         const int32_t *sel_idx, int32_t k,
+                                         float loss_scale, float mu,
+                                         void *const *sendbuf, float *chunk_l1, gf_stream stream)
+{
+    if (!pl) return GF_EINVAL;
+    // the scratch is private to this entry point: nothing another call left in a workspace is in it
+    if (phase & (GF_PHASE_SLOTS | GF_PHASE_DEFER_NORMS)) return GF_EINVAL;
+    if (gf_ws_total_bytes(pl) > static_cast<size_t>(GF_STATIC_SCRATCH_BYTES)) return GF_ELIMIT;
+    void *ws = nullptr;
+    const gf_status rc = static_scratch(&ws);
+    if (rc != GF_OK) return rc;
+    return fuse_pack(pl, phase, grads, pools, residual, sel_idx, k, loss_scale, mu, sendbuf, chunk_l1,
+                     0, pl->n_tiles, ws, stream);
+}

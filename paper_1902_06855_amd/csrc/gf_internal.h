@@ -136,7 +136,8 @@ inline size_t gf_ws_scores_bytes(const gf_plan *p)
     return (static_cast<size_t>(p->n_chunks) * sizeof(float) + 255) / 256 * 256;
 }
 // Sub-tiles per tile in gf_fuse_pack, and the partial chunk norms they leave
-// behind (one double per worker, chunk and sub-tile) when there are several.
+// behind (one double per worker, chunk and sub-tile) when there are several, or
+// when the caller leaves the norms in the workspace for gf_chunk_score_select.
 inline int32_t gf_fuse_subs(const gf_plan *p)
 {
     return p->tile <= GF_FUSE_SUB ? 1 : (p->tile + GF_FUSE_SUB - 1) / GF_FUSE_SUB;
@@ -147,9 +148,8 @@ inline int32_t gf_fuse_sub_len(const gf_plan *p) { return p->tile < GF_FUSE_SUB 
 inline size_t gf_ws_l1part_off(const gf_plan *p) { return gf_ws_slotmap_bytes(p) + gf_ws_scores_bytes(p); }
 inline size_t gf_ws_l1part_bytes(const gf_plan *p)
 {
-    const int32_t subs = gf_fuse_subs(p);
-    if (p->chunk == 0 || subs == 1) return 0;
-    return (static_cast<size_t>(p->P) * p->n_chunks * subs * sizeof(double) + 255) / 256 * 256;
+    if (p->chunk == 0) return 0;
+    return (static_cast<size_t>(p->P) * p->n_chunks * gf_fuse_subs(p) * sizeof(double) + 255) / 256 * 256;
 }
 inline size_t gf_ws_total_bytes(const gf_plan *p)
 {

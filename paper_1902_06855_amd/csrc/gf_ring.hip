@@ -39,6 +39,9 @@ struct RingArgs {
     int32_t M, G;                     // ring participants (= segments) and ranks per group; M * G = P
     int32_t blocks_per_segment;       // CSC plans: workgroups per segment of a full bucket
     int64_t bucket_span;              // CSC plans: elements per full bucket of the packed buffer
+    // CSC plans, optional filter: only the buckets whose last chunk lies in [chunk_lo, chunk_hi)
+    const int32_t *sel;               // the selection the buffer was packed with (ascending), or NULL: every bucket
+    int32_t k, chunks_per_bucket, chunk_lo, chunk_hi;
 };
 
 template <typename W> struct vec16;
@@ -105,6 +108,13 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
         const int r = item - b * per_bucket;
         lo = static_cast<int64_t>(b) * a.bucket_span;
         if (lo >= L) return;
+        if (a.sel) {
+            // the bucket is complete once its last chunk has been packed: it is reduced by the
+            // call whose range holds that chunk, and by no other
+            const int64_t after = (static_cast<int64_t>(b) + 1) * a.chunks_per_bucket;
+            const int32_t c = a.sel[(after < a.k ? after : a.k) - 1];
+            if (c < a.chunk_lo || c >= a.chunk_hi) return;
+        }
         hi = lo + a.bucket_span < L ? lo + a.bucket_span : L;
         const int64_t per = (hi - lo + M - 1) / M;
         seg = (per + A - 1) / A * A;
@@ -215,13 +225,20 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
 
 }  // namespace
 
-extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *sendbuf, int64_t L,
-                                        const int64_t *L_dev, void *reduced, void *const *allgather_out,
-                                        void *workspace, gf_stream stream)
+namespace {
+
+gf_status ring_reduce(const gf_plan *pl, const void *const *sendbuf, int64_t L, const int64_t *L_dev,
+                      const int32_t *sel_idx, int32_t k, int32_t chunk_lo, int32_t chunk_hi,
+                      void *reduced, void *const *allgather_out, gf_stream stream)
 {
-    (void)workspace;
     if (!pl || !sendbuf || !reduced || L < 0) return GF_EINVAL;
     const bool dense = pl->chunk == 0;
+    if (sel_idx) {
+        if (dense || k < 1 || k > pl->n_chunks || chunk_lo < 0 || chunk_hi > pl->n_chunks || chunk_lo > chunk_hi)
+            return GF_EINVAL;
+        if (L != static_cast<int64_t>(k) * pl->chunk) return GF_EINVAL;     // the capacity of k packed chunks
+        if (chunk_lo == chunk_hi) return GF_OK;
+    }
     if (dense && (L != pl->N || L_dev)) return GF_EINVAL;
     if (!dense && L > static_cast<int64_t>(pl->n_chunks) * pl->chunk) return GF_EINVAL;
     if (!pl->on_device) return GF_ESTATE;
@@ -234,6 +251,10 @@ extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *se
     a.allgather = allgather_out;
     a.L = L;
     a.L_dev = L_dev;
+    a.sel = sel_idx;
+    a.k = k;
+    a.chunk_lo = chunk_lo;
+    a.chunk_hi = chunk_hi;
     a.P = pl->P;
     a.M = pl->ring_M;
     a.G = pl->P / pl->ring_M;
@@ -262,6 +283,7 @@ extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *se
         if (bps * pl->ring_M * n_buckets > (int64_t{1} << 30)) return GF_EINVAL;
         a.blocks_per_segment = static_cast<int32_t>(bps);
         a.bucket_span = span;
+        a.chunks_per_bucket = static_cast<int32_t>(span / pl->chunk);
         const dim3 grid(static_cast<unsigned>(bps * pl->ring_M * n_buckets));
         if (f16 && !hier) hipLaunchKernelGGL((k_ring<uint16_t, false, false>), grid, block, 0, st, a);
         else if (f16) hipLaunchKernelGGL((k_ring<uint16_t, false, true>), grid, block, 0, st, a);
@@ -270,4 +292,24 @@ extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *se
     }
     GF_LAUNCH_CHECK();
     return GF_OK;
+}
+
+}  // namespace
+
+extern "C" gf_status gf_ring_reduce_sim(const gf_plan *pl, const void *const *sendbuf, int64_t L,
+                                        const int64_t *L_dev, void *reduced, void *const *allgather_out,
+                                        void *workspace, gf_stream stream)
+{
+    (void)workspace;
+    return ring_reduce(pl, sendbuf, L, L_dev, nullptr, 0, 0, 0, reduced, allgather_out, stream);
+}
+
+extern "C" gf_status gf_ring_reduce_range(const gf_plan *pl, const void *const *sendbuf, int64_t L,
+                                          const int64_t *L_dev, const int32_t *sel_idx, int32_t k,
+                                          int32_t chunk_lo, int32_t chunk_hi, void *reduced,
+                                          void *const *allgather_out, void *workspace, gf_stream stream)
+{
+    (void)workspace;
+    if (!sel_idx) return GF_EINVAL;
+    return ring_reduce(pl, sendbuf, L, L_dev, sel_idx, k, chunk_lo, chunk_hi, reduced, allgather_out, stream);
 }

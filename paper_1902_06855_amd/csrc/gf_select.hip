@@ -14,7 +14,14 @@ constexpr int SEL_T = 1024;   // threads of the single selecting workgroup
 // the norm of the (identical) reduced values, each GPU dividing it by the GPU count before the
 // norms are summed over GPUs; every other chunk by the sum of the workers' local norms, rows
 // added in ascending order.
-__global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1, int32_t P, int32_t nc,
+// The local norms come either finished (l1, one float per worker and chunk) or, when gf_fuse_pack
+// left them in the workspace, as per-sub-tile partial sums (part, `subs` doubles per worker and
+// chunk) that are finished here exactly as gf_fuse_pack would have: sub-tiles added in ascending
+// order in fp64, rounded once to fp32.
+// SUBS: -1 finished norms; 1..4 that many partial sums per norm; 0 any number of them (`subs`).
+template <int SUBS>
+__global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1, const double *__restrict__ part,
+                                                    int32_t subs, int32_t P, int32_t nc,
                                                     const float *__restrict__ red_l1,
                                                     const int32_t *__restrict__ prev_sel, int32_t k_prev,
                                                     float *__restrict__ score)
@@ -35,17 +42,34 @@ __global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1
             return;
         }
     }
-    // eight row loads are in flight at a time
+    // the norm of worker p, finished
+    auto norm = [&](int p) {
+        if constexpr (SUBS < 0) {
+            return l1[static_cast<int64_t>(p) * nc + c];
+        } else {
+            const int n_sub = SUBS > 0 ? SUBS : subs;
+            const double *q = part + (static_cast<int64_t>(p) * nc + c) * n_sub;
+            double n = q[0];
+            if constexpr (SUBS > 0) {
+#pragma unroll
+                for (int i = 1; i < SUBS; ++i) n += q[i];
+            } else {
+                for (int i = 1; i < n_sub; ++i) n += q[i];
+            }
+            return static_cast<float>(n);
+        }
+    };
+    // eight workers' loads are in flight at a time
     double s = 0.0;
     int p = 0;
     for (; p + 8 <= P; p += 8) {
         float x[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = l1[static_cast<int64_t>(p + u) * nc + c];
+        for (int u = 0; u < 8; ++u) x[u] = norm(p + u);
 #pragma unroll
         for (int u = 0; u < 8; ++u) s += static_cast<double>(x[u]);
     }
-    for (; p < P; ++p) s += static_cast<double>(l1[static_cast<int64_t>(p) * nc + c]);
+    for (; p < P; ++p) s += static_cast<double>(norm(p));
     score[c] = static_cast<float>(s);
 }
 
@@ -92,7 +116,7 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *wave_t
 __global__ __launch_bounds__(SEL_T) void k_select(const float *__restrict__ score, int32_t nc, int32_t k,
                                                   int32_t C, int64_t N,
                                                   int32_t *__restrict__ sel, uint8_t *__restrict__ mask,
-                                                  int64_t *__restrict__ packed_len)
+                                                  int64_t *__restrict__ packed_len, int32_t *__restrict__ slotmap)
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_tot[SEL_T / 64];
@@ -142,8 +166,10 @@ __global__ __launch_bounds__(SEL_T) void k_select(const float *__restrict__ scor
         const uint32_t eq_before = eq_base + (ex >> 16);
         if (c < nc) {
             const bool take = gt || (eq && eq_before < r);
-            if (take) sel[gt_before + (eq_before < r ? eq_before : r)] = c;
+            const int32_t rank = static_cast<int32_t>(gt_before + (eq_before < r ? eq_before : r));
+            if (take) sel[rank] = c;
             if (mask) mask[c] = take ? 1 : 0;
+            if (slotmap) slotmap[c] = take ? rank : -1;      // what gf_fuse_pack needs to pack this selection
             if (packed_len && c == nc - 1) {
                 const int64_t last_len = N - static_cast<int64_t>(nc - 1) * C;
                 *packed_len = static_cast<int64_t>(k) * C - (take ? C - last_len : 0);
@@ -161,24 +187,36 @@ extern "C" gf_status gf_chunk_score_select(const gf_plan *pl, const float *chunk
                                            int32_t k, float *scores, int32_t *sel_idx, uint8_t *mask,
                                            int64_t *packed_len, void *workspace, gf_stream stream)
 {
-    if (!pl || !chunk_l1 || !sel_idx) return GF_EINVAL;
+    if (!pl || !sel_idx) return GF_EINVAL;
     if (pl->chunk == 0 || k < 1 || k > pl->n_chunks) return GF_EINVAL;
     if (prev_sel && (!reduced_l1 || k_prev < 1 || k_prev > pl->n_chunks)) return GF_EINVAL;
-    // the score vector lives in the workspace when the caller does not want it
-    if (!scores) {
-        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return GF_EINVAL;
-        scores = reinterpret_cast<float *>(static_cast<char *>(workspace) + gf_ws_scores_off(pl));
-    }
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return GF_EINVAL;
+    // the workspace holds the score vector when the caller does not want it, the norms when
+    // gf_fuse_pack left them there, and receives the slot map of the new selection
+    if ((!scores || !chunk_l1) && !workspace) return GF_EINVAL;
+    char *ws = static_cast<char *>(workspace);
+    if (!scores) scores = reinterpret_cast<float *>(ws + gf_ws_scores_off(pl));
+    const double *part = chunk_l1 ? nullptr : reinterpret_cast<const double *>(ws + gf_ws_l1part_off(pl));
+    int32_t *slotmap = ws ? reinterpret_cast<int32_t *>(ws + gf_ws_slotmap_off()) : nullptr;
     if (!pl->on_device) return GF_ESTATE;
     GF_CHECK_DEVICE(pl);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int32_t nc = pl->n_chunks;
 
-    hipLaunchKernelGGL(k_score, dim3((nc + GF_BLOCK - 1) / GF_BLOCK), dim3(GF_BLOCK), 0, st,
-                       chunk_l1, pl->P, nc, reduced_l1, prev_sel, k_prev, scores);
+    const int32_t subs = gf_fuse_subs(pl);
+    const dim3 grid((nc + GF_BLOCK - 1) / GF_BLOCK), block(GF_BLOCK);
+#define GF_SCORE(S) hipLaunchKernelGGL(k_score<S>, grid, block, 0, st, chunk_l1, part, subs, pl->P, nc, reduced_l1, \
+                                       prev_sel, k_prev, scores)
+    if (chunk_l1) GF_SCORE(-1);
+    else if (subs == 1) GF_SCORE(1);
+    else if (subs == 2) GF_SCORE(2);
+    else if (subs == 3) GF_SCORE(3);
+    else if (subs == 4) GF_SCORE(4);
+    else GF_SCORE(0);
+#undef GF_SCORE
     GF_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_T), 0, st,
-                       scores, nc, k, pl->chunk, pl->N, sel_idx, mask, packed_len);
+                       scores, nc, k, pl->chunk, pl->N, sel_idx, mask, packed_len, slotmap);
     GF_LAUNCH_CHECK();
     return GF_OK;
 }

@@ -23,6 +23,9 @@ struct UnpackArgs {
     int64_t N;
     int32_t tile;
     float alpha, momentum, lr;
+    // optional filter (CSC plans): only the chunks of packed buckets whose last chunk lies in
+    // [chunk_lo, chunk_hi); chunks_per_bucket = 0 switches it off
+    int32_t k, chunks_per_bucket, chunk_lo, chunk_hi;
 };
 
 // log2 of the consecutive tiles one XCD takes
@@ -122,6 +125,11 @@ template <typename W, bool UPD, int NT>
 __global__ __launch_bounds__(NT) void k_unpack(const UnpackArgs a)
 {
     const int j = gf_xcd_order(blockIdx.x, gridDim.x, UNPACK_GRP_SHIFT);
+    if (a.chunks_per_bucket) {                       // uniform across the workgroup
+        const int64_t after = (static_cast<int64_t>(j / a.chunks_per_bucket) + 1) * a.chunks_per_bucket;
+        const int32_t c = a.sel_idx[(after < a.k ? after : a.k) - 1];
+        if (c < a.chunk_lo || c >= a.chunk_hi) return;
+    }
     const int tile = a.sel_idx ? a.sel_idx[j] : j;
     const int64_t tile_lo = static_cast<int64_t>(tile) * a.tile;
     const int64_t left = a.N - tile_lo;
@@ -211,6 +219,29 @@ extern "C" gf_status gf_unpack_apply(const gf_plan *pl, const void *reduced, int
     a.out_tensors = out_tensors;
     a.reduced_l1 = reduced_l1;
     a.alpha = alpha;
+    return unpack_common(pl, a, L, k, false, stream);
+}
+
+extern "C" gf_status gf_unpack_range(const gf_plan *pl, const void *reduced, int64_t L,
+                                     const int32_t *sel_idx, int32_t k, int32_t chunk_lo, int32_t chunk_hi,
+                                     float alpha, float *out_pool, void *const *out_tensors,
+                                     float *reduced_l1, void *workspace, gf_stream stream)
+{
+    (void)workspace;
+    if (!pl || !reduced || !sel_idx || (!out_pool && !out_tensors)) return GF_EINVAL;
+    if (pl->chunk == 0 || chunk_lo < 0 || chunk_hi > pl->n_chunks || chunk_lo > chunk_hi) return GF_EINVAL;
+    if (chunk_lo == chunk_hi) return GF_OK;
+    UnpackArgs a{};
+    a.reduced = reduced;
+    a.sel_idx = sel_idx;
+    a.out_pool = out_pool;
+    a.out_tensors = out_tensors;
+    a.reduced_l1 = reduced_l1;
+    a.alpha = alpha;
+    a.k = k;
+    a.chunks_per_bucket = static_cast<int32_t>(gf_csc_bucket_span(pl) / pl->chunk);
+    a.chunk_lo = chunk_lo;
+    a.chunk_hi = chunk_hi;
     return unpack_common(pl, a, L, k, false, stream);
 }
 

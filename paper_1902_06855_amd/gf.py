@@ -30,15 +30,15 @@ _lib = C.CDLL(LIB_PATH)
 GF_OK, GF_EINVAL, GF_ENOMEM, GF_EHIP, GF_ESTATE, GF_ELIMIT = 0, 1, 2, 3, 4, 5
 GF_STATIC_SCRATCH_BYTES = 4 << 20
 GF_WIRE_F16, GF_WIRE_F32 = 0, 1
-GF_PHASE_ACCUM, GF_PHASE_PACK = 1, 2
+GF_PHASE_ACCUM, GF_PHASE_PACK, GF_PHASE_SLOTS, GF_PHASE_DEFER_NORMS = 1, 2, 4, 8
 
 EXPORTS = (
     "gf_status_string", "gf_plan_create", "gf_plan_set_grad_type", "gf_plan_set_reduce_groups",
     "gf_plan_to_device", "gf_plan_destroy", "gf_plan_info",
     "gf_plan_layout", "gf_plan_ring_segment", "gf_plan_tiles", "gf_plan_tile_pieces",
-    "gf_plan_workspace_bytes", "gf_plan_warmup_k", "gf_fuse_pack", "gf_fuse_pack_static", "gf_chunk_score_select",
-    "gf_ring_reduce_sim",
-    "gf_unpack_apply", "gf_unpack_sgd_update",
+    "gf_plan_workspace_bytes", "gf_plan_warmup_k", "gf_fuse_pack", "gf_fuse_pack_range", "gf_fuse_pack_static",
+    "gf_chunk_score_select", "gf_ring_reduce_sim", "gf_ring_reduce_range", "gf_unpack_apply", "gf_unpack_range",
+    "gf_unpack_sgd_update",
 )
 
 _vp, _i32, _i64, _u32, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_float
@@ -66,10 +66,14 @@ _plan_tile_pieces = _sig("gf_plan_tile_pieces", _i32, _vp, _i32, _i32, C.POINTER
 _plan_workspace_bytes = _sig("gf_plan_workspace_bytes", C.c_size_t, _vp)
 _plan_warmup_k = _sig("gf_plan_warmup_k", _i32, _vp, C.c_double, _i64, _i64)
 _fuse_pack = _sig("gf_fuse_pack", C.c_int, _vp, _u32, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp, _vp)
+_fuse_pack_range = _sig("gf_fuse_pack_range", C.c_int, _vp, _u32, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _i32, _i32,
+                        _vp, _vp)
 _fuse_pack_static = _sig("gf_fuse_pack_static", C.c_int, _vp, _u32, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp)
 _chunk_score_select = _sig("gf_chunk_score_select", C.c_int, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
                            _vp, _vp, _vp)
 _ring_reduce_sim = _sig("gf_ring_reduce_sim", C.c_int, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp)
+_ring_reduce_range = _sig("gf_ring_reduce_range", C.c_int, _vp, _vp, _i64, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp)
+_unpack_range = _sig("gf_unpack_range", C.c_int, _vp, _vp, _i64, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp)
 _unpack_apply = _sig("gf_unpack_apply", C.c_int, _vp, _vp, _i64, _vp, _i32, _f32, _vp, _vp, _vp, _vp, _vp)
 _unpack_sgd_update = _sig("gf_unpack_sgd_update", C.c_int, _vp, _vp, _i64, _vp, _i32, _f32, _f32, _f32, _vp, _vp, _vp,
                           _vp, _vp, _vp, _vp, _vp)
@@ -204,6 +208,15 @@ def gf_fuse_pack(plan: Plan, phase: int, *, grads=None, pools=None, residual=Non
                       _stream(stream)), "gf_fuse_pack")
 
 
+def gf_fuse_pack_range(plan: Plan, phase: int, chunk_lo: int, chunk_hi: int, *, grads=None, pools=None, residual=None,
+                       sel_idx=None, k: int = 0, loss_scale: float = 1.0, mu: float = 1.0, sendbuf=None, chunk_l1=None,
+                       workspace=None, stream=None) -> None:
+    """gf_fuse_pack over the chunks [chunk_lo, chunk_hi) only."""
+    _check(_fuse_pack_range(plan.handle, int(phase), _dptr(grads), _dptr(pools), _dptr(residual), _dptr(sel_idx),
+                            int(k), float(loss_scale), float(mu), _dptr(sendbuf), _dptr(chunk_l1), int(chunk_lo),
+                            int(chunk_hi), _dptr(workspace), _stream(stream)), "gf_fuse_pack_range")
+
+
 def gf_fuse_pack_static(plan: Plan, phase: int, *, grads=None, pools=None, residual=None, sel_idx=None, k: int = 0,
                         loss_scale: float = 1.0, mu: float = 1.0, sendbuf=None, chunk_l1=None, stream=None) -> None:
     """gf_fuse_pack with the library's own fixed scratch instead of a workspace (allocates nothing)."""
@@ -212,7 +225,7 @@ def gf_fuse_pack_static(plan: Plan, phase: int, *, grads=None, pools=None, resid
                              _stream(stream)), "gf_fuse_pack_static")
 
 
-def gf_chunk_score_select(plan: Plan, chunk_l1, *, reduced_l1=None, prev_sel=None, k_prev: int = 0, k: int,
+def gf_chunk_score_select(plan: Plan, chunk_l1=None, *, reduced_l1=None, prev_sel=None, k_prev: int = 0, k: int,
                           scores=None, sel_idx, mask=None, packed_len=None, workspace=None, stream=None) -> None:
     _check(_chunk_score_select(plan.handle, _dptr(chunk_l1), _dptr(reduced_l1), _dptr(prev_sel), int(k_prev),
                                int(k), _dptr(scores), _dptr(sel_idx), _dptr(mask), _dptr(packed_len),
@@ -223,6 +236,21 @@ def gf_ring_reduce_sim(plan: Plan, sendbuf, L: int, reduced, *, L_dev=None, allg
                        stream=None) -> None:
     _check(_ring_reduce_sim(plan.handle, _dptr(sendbuf), int(L), _dptr(L_dev), _dptr(reduced),
                             _dptr(allgather_out), _dptr(workspace), _stream(stream)), "gf_ring_reduce_sim")
+
+
+def gf_ring_reduce_range(plan: Plan, sendbuf, L: int, reduced, sel_idx, k: int, chunk_lo: int, chunk_hi: int, *,
+                         L_dev=None, allgather_out=None, workspace=None, stream=None) -> None:
+    """The packed buckets completed by the sweep over chunks [chunk_lo, chunk_hi)."""
+    _check(_ring_reduce_range(plan.handle, _dptr(sendbuf), int(L), _dptr(L_dev), _dptr(sel_idx), int(k), int(chunk_lo),
+                              int(chunk_hi), _dptr(reduced), _dptr(allgather_out), _dptr(workspace), _stream(stream)),
+           "gf_ring_reduce_range")
+
+
+def gf_unpack_range(plan: Plan, reduced, L: int, sel_idx, k: int, chunk_lo: int, chunk_hi: int, *, alpha: float = 1.0,
+                    out_pool=None, out_tensors=None, reduced_l1=None, workspace=None, stream=None) -> None:
+    _check(_unpack_range(plan.handle, _dptr(reduced), int(L), _dptr(sel_idx), int(k), int(chunk_lo), int(chunk_hi),
+                         float(alpha), _dptr(out_pool), _dptr(out_tensors), _dptr(reduced_l1), _dptr(workspace),
+                         _stream(stream)), "gf_unpack_range")
 
 
 def gf_unpack_apply(plan: Plan, reduced, L: int, *, sel_idx=None, k: int = 0, alpha: float = 1.0, out_pool=None,

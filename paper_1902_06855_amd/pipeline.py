@@ -31,8 +31,12 @@ class Pipeline:
                  k: int = 0, mu: float = 1.0, wire: str = "f16", schedule: str = "lagged",
                  scatter_out: bool = False, allgather: bool = False, device: str = "cuda",
                  sgd: Optional[tuple] = None, k_max: Optional[int] = None, grad: str = "f32",
-                 zero_copy: bool = False, groups: int = 0):
+                 zero_copy: bool = False, groups: int = 0, fast: bool = True):
         assert schedule in ("lagged", "immediate")
+        # fast: the calls of an iteration hand the slot map and the unfinished chunk norms to each
+        # other through the workspace (two small launches fewer per iteration; `self.l1` is then
+        # never written).  The results are the same bit for bit.
+        self.fast = bool(fast)
         if zero_copy and not (chunk == 0 and grad == "f16" and wire == "f16"):
             raise ValueError("zero_copy needs a dense plan with fp16 pools on an fp16 wire")
         self.zero_copy = bool(zero_copy)
@@ -122,29 +126,34 @@ class Pipeline:
 
     # ------------------------------------------------------------- stages
     def accum(self) -> None:
-        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_ACCUM, grads=self.grads_tab, pools=self.pools_tab,
-                        residual=self.residual_tab, chunk_l1=self.l1, workspace=self.ws)
+        defer = gf.GF_PHASE_DEFER_NORMS if self.fast else 0
+        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_ACCUM | defer, grads=self.grads_tab, pools=self.pools_tab,
+                        residual=self.residual_tab, chunk_l1=None if self.fast else self.l1, workspace=self.ws)
 
     def select(self, after_allreduce: bool) -> None:
         """Choose self.sel (in place); after_allreduce scores the chunks just sent by their reduced norm."""
+        l1 = None if self.fast else self.l1          # fast: the norms are still in the workspace
         if after_allreduce:
-            gf.gf_chunk_score_select(self.plan, self.l1, reduced_l1=self.red_l1, prev_sel=self.sel, k_prev=self.k,
+            gf.gf_chunk_score_select(self.plan, l1, reduced_l1=self.red_l1, prev_sel=self.sel, k_prev=self.k,
                                      k=self.k_next, scores=self.scores, sel_idx=self.sel, mask=self.mask,
                                      packed_len=self.packed_len, workspace=self.ws)
         else:
-            gf.gf_chunk_score_select(self.plan, self.l1, k=self.k_next, scores=self.scores, sel_idx=self.sel,
+            gf.gf_chunk_score_select(self.plan, l1, k=self.k_next, scores=self.scores, sel_idx=self.sel,
                                      mask=self.mask, packed_len=self.packed_len, workspace=self.ws)
         self.k = self.k_next
 
     def pack(self) -> None:
-        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_PACK, residual=self.residual_tab, sel_idx=self.sel, k=self.k,
+        # self.sel always comes from the last select() on this workspace, which left its slot map there
+        slots = gf.GF_PHASE_SLOTS if self.fast else 0
+        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_PACK | slots, residual=self.residual_tab, sel_idx=self.sel, k=self.k,
                         loss_scale=self.S, mu=self.mu, sendbuf=self.send_tab, workspace=self.ws)
 
     def fused(self) -> None:
-        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_ACCUM | gf.GF_PHASE_PACK, grads=self.grads_tab,
+        extra = (gf.GF_PHASE_SLOTS | gf.GF_PHASE_DEFER_NORMS) if self.fast else 0
+        gf.gf_fuse_pack(self.plan, gf.GF_PHASE_ACCUM | gf.GF_PHASE_PACK | extra, grads=self.grads_tab,
                         pools=self.pools_tab, residual=self.residual_tab, sel_idx=self.sel, k=self.k,
-                        loss_scale=self.S, mu=self.mu, sendbuf=self.send_tab, chunk_l1=self.l1,
-                        workspace=self.ws)
+                        loss_scale=self.S, mu=self.mu, sendbuf=self.send_tab,
+                        chunk_l1=None if self.fast else self.l1, workspace=self.ws)
 
     def cast_dense(self) -> None:
         gf.gf_fuse_pack(self.plan, gf.GF_PHASE_ACCUM | gf.GF_PHASE_PACK, grads=self.grads_tab,
@@ -303,6 +312,90 @@ class OverlappedDense:
     def capture(self) -> "torch.cuda.CUDAGraph":
         """The whole bucket-by-bucket iteration (side streams forked from and joined to the current
         one, no arrival events) as one HIP graph: takes the host's launch rate out of the picture."""
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step()
+        return graph
+
+
+class OverlappedCsc:
+    """Coarse-grained sparse communication with the enable-overlap setting (Section 3.2: "if an
+    important chunk is filled, CSC copies its data to a buffer; when the buffer size is greater
+    than a given threshold, CSC starts an allreduce"; Section 3.1): the pool is swept range by
+    range in generation order, each range as soon as its gradients exist, and every bucket of the
+    packed buffer is reduced and unpacked right after the sweep that completed it, while the next
+    ranges are still being swept.
+
+    Two side streams: one runs the sweeps (gf_fuse_pack_range) in order, the other the
+    allreduce and unpack of the buckets each sweep completed (gf_ring_reduce_range,
+    gf_unpack_range), which decide on the device, from the selection, which buckets those are.
+    The host therefore never reads the selection, and a whole iteration can be recorded in a graph.
+    Iteration 0 (the selection needs every norm first) and the selection at the end of every
+    iteration run as in `Pipeline`.  The results are those of `Pipeline` bit for bit.  It
+    computes nothing itself."""
+
+    def __init__(self, sizes: Sequence[int], P: int, chunk: int, theta: int, loss_scale: float, k: int,
+                 boundaries: Sequence[int], mu: float = 1.0, wire: str = "f16", device: str = "cuda",
+                 grad: str = "f32", groups: int = 0, scatter_out: bool = False):
+        if not chunk:
+            raise ValueError("a plan with chunks is needed (dense plans: OverlappedDense)")
+        self.pipe = Pipeline(sizes, P, chunk, theta, loss_scale, k=k, mu=mu, wire=wire, schedule="lagged",
+                             scatter_out=scatter_out, device=device, grad=grad, groups=groups, fast=True)
+        nc = self.pipe.n_chunks
+        self.bounds = [int(b) for b in boundaries]
+        if not self.bounds or self.bounds != sorted(set(self.bounds)) or self.bounds[0] < 1 or self.bounds[-1] != nc:
+            raise ValueError("boundaries: ascending chunk indices, the last one n_chunks")
+        self.sweep_stream = torch.cuda.Stream(device=device)       # default priority
+        self.reduce_stream = torch.cuda.Stream(device=device)
+
+    @property
+    def n_ranges(self) -> int:
+        return len(self.bounds)
+
+    def step(self, ready: Optional[Sequence[torch.cuda.Event]] = None) -> None:
+        """One iteration.  ready[r], if given, is an event recorded once the gradients of chunk
+        range r exist; the sweep of that range waits for it (and for the sweeps before it).
+        Returns without synchronising; the current stream waits for everything."""
+        p = self.pipe
+        if p.t == 0:
+            if ready is not None:
+                torch.cuda.current_stream().wait_event(ready[-1])
+            p.step()
+            return
+        cur = torch.cuda.current_stream()
+        start = torch.cuda.Event()
+        start.record(cur)
+        self.sweep_stream.wait_event(start)
+        self.reduce_stream.wait_event(start)
+        phase = gf.GF_PHASE_ACCUM | gf.GF_PHASE_PACK | gf.GF_PHASE_SLOTS | gf.GF_PHASE_DEFER_NORMS
+        lo = 0
+        for r, hi in enumerate(self.bounds):
+            if ready is not None:
+                self.sweep_stream.wait_event(ready[r])
+            with torch.cuda.stream(self.sweep_stream):
+                gf.gf_fuse_pack_range(p.plan, phase, lo, hi, grads=p.grads_tab, pools=p.pools_tab,
+                                      residual=p.residual_tab, sel_idx=p.sel, k=p.k, loss_scale=p.S, mu=p.mu,
+                                      sendbuf=p.send_tab, workspace=p.ws)
+                swept = torch.cuda.Event()
+                swept.record(self.sweep_stream)
+            self.reduce_stream.wait_event(swept)
+            with torch.cuda.stream(self.reduce_stream):
+                gf.gf_ring_reduce_range(p.plan, p.send_tab, p.cap, p.reduced, p.sel, p.k, lo, hi,
+                                        L_dev=p.packed_len, allgather_out=p.ag_tab, workspace=p.ws)
+                gf.gf_unpack_range(p.plan, p.reduced, p.cap, p.sel, p.k, lo, hi, alpha=p.alpha, out_pool=p.out_pool,
+                                   out_tensors=p.out_tab, reduced_l1=p.red_l1, workspace=p.ws)
+            lo = hi
+        cur.wait_stream(self.sweep_stream)
+        cur.wait_stream(self.reduce_stream)
+        p.select(True)
+        p.t += 1
+
+    def capture(self) -> "torch.cuda.CUDAGraph":
+        """A steady-state iteration (both side streams forked from and joined to the current one, no
+        arrival events) as one HIP graph.  The graph stays valid from iteration to iteration: which
+        buckets a call reduces is decided on the device."""
+        if self.pipe.t == 0:
+            raise ValueError("the first iteration is not a steady-state one")
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             self.step()

@@ -132,7 +132,9 @@ def test_csc_full_size_sampled(mods, name, groups):
     k = w.k_for(nc)
     sig = wl.sigma_table(w)
     gsets = [wl.gradients(w, t, device="cuda", sig=sig) for t in range(2)]
-    pipe = pl.Pipeline(w.sizes, P, C, w.theta, w.loss_scale, k=k, mu=w.mu, schedule="lagged", groups=groups)
+    # iteration 0 materialises the per-worker chunk norms (checked below); iteration 1 runs as the
+    # benchmark does, the calls handing slot map and unfinished norms over through the workspace
+    pipe = pl.Pipeline(w.sizes, P, C, w.theta, w.loss_scale, k=k, mu=w.mu, schedule="lagged", groups=groups, fast=False)
     assert pipe.n_chunks == nc
     sync = torch.cuda.synchronize
     alpha = np.float32(1.0) / np.float32(w.loss_scale)
@@ -244,13 +246,27 @@ def test_csc_full_size_sampled(mods, name, groups):
     g1 = g_chunks(1, sample)
     acc1 = {c: ob.accumulate(np.ascontiguousarray(g1[c]), np.ascontiguousarray(st0[c][0])) for c in sample}
     pipe.set_gradients(gsets[1])
+    pipe.fast = True
+    pipe.l1.fill_(-1.0)
     pipe.fused(); sync()
-    l1_1 = pipe.l1.cpu().numpy().reshape(P, nc).copy()
-    check_norms(1, l1_1, acc1, sample)
+    assert torch.all(pipe.l1 == -1.0)                  # the norms stay in the workspace
     st1 = check_pack(1, sel1, acc1, sample)
     pipe.out_pool.fill_(-9.0)
     pipe.ring(); pipe.unpack(); sync()
     red_l1_1 = pipe.red_l1.cpu().numpy().copy()
     check_unpack(1, st1, red_l1_1, sample)
     pipe.select(True); sync()
-    check_selection(l1_1, sel1, red_l1_1)
+    # scores: a sent chunk by its reduced norm (the checker's function, bit for bit), any other by the
+    # sum of the workers' norms (finished from the workspace; 1e-5); selection = top-k of those scores
+    sc = pipe.scores.cpu().numpy().copy()
+    for c in sample:
+        sent, j = is_in(sel1, c)
+        if sent:
+            want = ob.score(np.zeros((P, 1), dtype=np.float32), first, red_l1_1[j:j + 1])[0]
+            assert u32(np.float32(sc[c])) == u32(np.float32(want)), f"score of sent chunk {c}"
+        else:
+            norms = ob.chunk_l1(np.ascontiguousarray(acc1[c]), C)        # [P, 1]
+            assert np.isclose(sc[c], ob.score(norms)[0], rtol=RTOL, atol=0), f"score of chunk {c}"
+    sel2 = pipe.sel.cpu().numpy().copy()
+    assert np.array_equal(sel2, ob.select(sc, k)[0]), "selection is the checker's top-k of the scores"
+    assert np.array_equal(np.flatnonzero(pipe.mask.cpu().numpy()), sel2)

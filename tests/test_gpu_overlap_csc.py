@@ -1,0 +1,212 @@
+"""Coarse-grained sparse communication issued while the pool is still filling
+(Section 3.2: important chunks are packed as they fill, a bucket of the buffer is
+allreduced once more than theta is waiting; Section 3.1: enable-overlap), through
+the C ABI's range calls, against the CPU checker's whole iteration: bit-identical
+send buffers, historical gradients, reduced buffer, outputs and selections."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import binding as ob, pipeline as op
+from paper_1902_06855_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gfm():
+    from paper_1902_06855_amd import gf, pipeline
+    return gf, pipeline
+
+
+def bits(a):
+    a = np.ascontiguousarray(a)
+    return a.view({2: np.uint16, 4: np.uint32}[a.dtype.itemsize])
+
+
+def same(gpu: torch.Tensor, ref: np.ndarray, what: str):
+    g = gpu.detach().cpu().numpy()
+    assert g.shape == ref.shape, f"{what}: shape {g.shape} vs {ref.shape}"
+    bad = np.flatnonzero(bits(g).ravel() != bits(ref).ravel())
+    assert bad.size == 0, f"{what}: {bad.size} of {g.size} differ, first at {bad[:5]}"
+
+
+def pools_of(w, t):
+    g = wl.gradients(w, t)
+    return g, np.stack([op.fuse([x.numpy() for x in row], w.sizes) for row in g])
+
+
+def check_iteration(ov, w, st, pools, k, theta, groups, what):
+    """One checker iteration on the same gradients; compares everything the GPU left behind."""
+    p = ov.pipe
+    out = np.full(w.N, np.float32(-6.0))
+    r = op.csc_iteration(st, pools, w.chunk, k, w.loss_scale, w.mu, "lagged", w.wire, out=out, theta=theta,
+                         groups=groups)
+    L = r["send"].shape[1]
+    it = torch.int16 if w.wire == "f16" else torch.int32
+    nt = np.int16 if w.wire == "f16" else np.int32
+    for q in range(w.P):
+        same(p.send[q][:L].view(it), r["send"][q].view(nt), f"{what} send[{q}]")
+        same(p.residual[q], st.hg[q], f"{what} hg[{q}]")
+    same(p.reduced[:L].view(it), r["reduced"].view(nt), f"{what} reduced")
+    same(p.out_pool, out, f"{what} out")
+    assert np.array_equal(p.sel.cpu().numpy()[:k], r["sel_next"]), f"{what} selection"
+    return r
+
+
+CASES = [
+    # sizes, P, chunk, density, cuts (fractions of n_chunks)
+    ([50, 7, 701, 33, 1201, 64, 5, 4099], 3, 96, 0.4, (0.2, 0.5, 0.55, 0.9)),
+    ([20000 * 3 + 4, 100, 20000 * 2, 5000, 12345, 30000], 2, 20000, 0.5, (0.34, 0.67)),     # three sub-tiles per chunk
+    ([8192 * 5, 64, 8192 * 7 + 8, 1000], 4, 8192, 0.3, (0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+def test_range_by_range_iterations_equal_the_checker(gfm, case, wire, mode):
+    gf, pl = gfm
+    sizes, P, C, density, fracs = CASES[case]
+    for theta_chunks, groups in ((0, 0), (2, 0), (1 << 20, 0), (1, 2 if P == 4 else 1)):   # last: hierarchical order
+        theta = theta_chunks * C if theta_chunks < (1 << 20) else 1 << 40
+        w = wl.Workload("ovcsc", sizes, P=P, chunk=C, density=density, loss_scale=64.0, theta=theta, mu=0.9, wire=wire)
+        nc = ob.n_chunks(w.N, C)
+        k = w.k_for(nc)
+        bounds = sorted(set(max(1, int(f * nc)) for f in fracs) | {nc})
+        ov = pl.OverlappedCsc(w.sizes, P, C, theta, w.loss_scale, k, bounds, mu=w.mu, wire=wire, groups=groups)
+        st = op.new_state(P, w.N)
+        for t in range(4):
+            g, pools = pools_of(w, t)
+            if mode == "gather":
+                ov.pipe.set_gradients([[x.cuda() for x in row] for row in g])
+            else:
+                ov.pipe.set_pools([torch.from_numpy(pools[q]).cuda() for q in range(P)])
+            ov.pipe.out_pool.fill_(-6.0)
+            ov.step()
+            torch.cuda.synchronize()
+            r = check_iteration(ov, w, st, pools, k, theta, groups, f"case {case} theta {theta} t={t}")
+            if theta_chunks == 2 and k > 3:
+                assert len(r["packed_bucket_lo"]) >= 2       # several allreduces per iteration
+
+
+def test_a_sweep_waits_for_its_own_gradients_only(gfm):
+    """The pool is written range by range on a slow producer stream (as backward would), each range
+    followed by its arrival event; no sweep may read its range earlier, no bucket may be reduced
+    before its chunks are packed."""
+    gf, pl = gfm
+    C, P = 8192, 2
+    sizes = [C * 40 + 24, 1000, C * 30, 64, C * 25 + 8]
+    for theta in (3 * C, 1 << 40):
+        w = wl.Workload("arrive", sizes, P=P, chunk=C, density=0.3, loss_scale=32.0, theta=theta)
+        nc = ob.n_chunks(w.N, C)
+        k = w.k_for(nc)
+        bounds = [nc // 5, 2 * nc // 5, 3 * nc // 5, 4 * nc // 5, nc]
+        ov = pl.OverlappedCsc(w.sizes, P, C, theta, w.loss_scale, k, bounds)
+        st = op.new_state(P, w.N)
+        live = [torch.zeros(w.N, device="cuda") for _ in range(P)]       # what the sweeps read
+        ov.pipe.set_pools(live)
+        producer = torch.cuda.Stream()
+        for t in range(3):
+            _, pools = pools_of(w, t)
+            staged = [torch.from_numpy(pools[q]).cuda() for q in range(P)]
+            for q in range(P):
+                live[q].fill_(float("nan"))                                  # reading early poisons the result
+            ov.pipe.out_pool.fill_(-6.0)
+            torch.cuda.synchronize()
+            ready = [torch.cuda.Event() for _ in bounds]
+            with torch.cuda.stream(producer):
+                lo = 0
+                for r_, hi in enumerate(bounds):
+                    a, b = lo * C, min(w.N, hi * C)
+                    for _ in range(20):                                      # make the producer slow
+                        for q in range(P):
+                            live[q][a:b].copy_(staged[q][a:b], non_blocking=True)
+                    ready[r_].record(producer)
+                    lo = hi
+            ov.step(ready=ready)
+            torch.cuda.synchronize()
+            check_iteration(ov, w, st, pools, k, theta, 0, f"theta {theta} t={t}")
+
+
+@pytest.mark.parametrize("theta_chunks", [1, 1 << 20])
+def test_one_graph_serves_every_iteration(gfm, theta_chunks):
+    """A steady-state iteration recorded once; the selection changes from iteration to iteration and
+    the replays follow it (which buckets a call reduces is decided on the device).  Unrelated eager
+    work and synchronisations between the replays."""
+    gf, pl = gfm
+    C, P = 512, 3
+    sizes = [C * 9 + 4, 100, C * 14, 40, C * 6 + 8, 7]
+    theta = theta_chunks * C if theta_chunks < (1 << 20) else 1 << 40
+    w = wl.Workload("graph", sizes, P=P, chunk=C, density=0.3, loss_scale=16.0, theta=theta, mu=0.9)
+    nc = ob.n_chunks(w.N, C)
+    k = w.k_for(nc)
+    bounds = [nc // 4, nc // 2, 3 * nc // 4, nc]
+    ov = pl.OverlappedCsc(w.sizes, P, C, theta, w.loss_scale, k, bounds, mu=w.mu)
+    st = op.new_state(P, w.N)
+    live = [torch.zeros(w.N, device="cuda") for _ in range(P)]
+    ov.pipe.set_pools(live)
+    graph = None
+    selections = []
+    for t in range(7):
+        _, pools = pools_of(w, t)
+        for q in range(P):
+            live[q].copy_(torch.from_numpy(pools[q]))
+        ov.pipe.out_pool.fill_(-6.0)
+        if t == 0:
+            ov.step()                                        # two-pass first iteration
+        elif t == 1:
+            graph = ov.capture()                             # recording does not run it
+            graph.replay()
+        else:
+            graph.replay()
+        torch.cuda.synchronize()
+        torch.randn(1 << 14, device="cuda").sum().item()     # unrelated eager work in between
+        r = check_iteration(ov, w, st, pools, k, theta, 0, f"theta {theta} t={t}")
+        selections.append(tuple(r["sel_next"].tolist()))
+    assert len(set(selections)) > 2                          # the selection did move under the graph
+
+
+def test_range_calls_without_the_hand_overs_tile_to_the_whole_call(gfm):
+    """gf_fuse_pack_range with neither modifier bit (every call rebuilds the slot map and finishes
+    the norms of its own chunks): ranges that tile the pool leave the bytes of one gf_fuse_pack,
+    which the other tests hold against the checker."""
+    gf, pl = gfm
+    for sizes, P, C in (([20000 * 3 + 4, 100, 20000 * 2, 5000, 12345], 3, 20000), ([50, 7, 701, 33, 1201, 64, 5], 2, 96)):
+        plan = gf.Plan(sizes, 1 << 40, C, P)
+        nc, N = plan.n_chunks, plan.N
+        k = max(1, nc // 3)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(5)
+        pools = [torch.randn(N, generator=g, device="cuda") * 1e-2 for _ in range(P)]
+        hg0 = [torch.randn(N, generator=g, device="cuda") * 1e-3 for _ in range(P)]
+        sel = torch.sort(torch.randperm(nc, generator=g, device="cuda")[:k]).values.to(torch.int32)
+        ws = plan.workspace()
+
+        def run(ranges):
+            res = [h.clone() for h in hg0]
+            send = [torch.full((k * C,), 3.0, dtype=torch.float16, device="cuda") for _ in range(P)]
+            l1 = torch.full((P * nc,), -1.0, device="cuda")
+            args = dict(pools=gf.ptr_table(pools), residual=gf.ptr_table(res), sel_idx=sel, k=k, loss_scale=8.0, mu=0.5,
+                        sendbuf=gf.ptr_table(send), chunk_l1=l1, workspace=ws)
+            phase = gf.GF_PHASE_ACCUM | gf.GF_PHASE_PACK
+            if ranges is None:
+                gf.gf_fuse_pack(plan, phase, **args)
+            else:
+                for lo, hi in ranges:
+                    gf.gf_fuse_pack_range(plan, phase, lo, hi, **args)
+            torch.cuda.synchronize()
+            return res, send, l1
+
+        want = run(None)
+        cut = sorted({1, nc // 3, nc // 3 + 1, 2 * nc // 3, nc} - {0})
+        got = run(list(zip([0] + cut[:-1], cut)))
+        for q in range(P):
+            assert torch.equal(got[0][q].view(torch.int32), want[0][q].view(torch.int32)), f"hg[{q}]"
+            assert torch.equal(got[1][q].view(torch.int16), want[1][q].view(torch.int16)), f"send[{q}]"
+        assert torch.equal(got[2].view(torch.int32), want[2].view(torch.int32)) and torch.all(want[2] >= 0)
+        # an empty range does nothing; a range past the pool is refused
+        gf.gf_fuse_pack_range(plan, gf.GF_PHASE_ACCUM, 2, 2, pools=gf.ptr_table(pools), residual=gf.ptr_table(hg0))
+        with pytest.raises(gf.GfError):
+            gf.gf_fuse_pack_range(plan, gf.GF_PHASE_ACCUM, 0, nc + 1, pools=gf.ptr_table(pools), residual=gf.ptr_table(hg0))
+        plan.close()

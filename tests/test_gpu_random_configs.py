@@ -43,7 +43,7 @@ def test_random_configuration(gfm, seed):
     nc = ob.n_chunks(w.N, w.chunk) if w.chunk else 0
     k = w.k_for(nc) if w.chunk else 0
     pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=k, mu=w.mu, wire=w.wire,
-                       schedule=c["schedule"], grad=c["grad"], groups=c["groups"])
+                       schedule=c["schedule"], grad=c["grad"], groups=c["groups"], fast=bool(seed % 2))
     st = op.new_state(w.P, w.N)
     it, nt = (torch.int16, np.int16) if w.wire == "f16" else (torch.int32, np.int32)
     what = f"seed {seed}: {c}"
