@@ -150,7 +150,11 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
             const __amdgpu_buffer_rsrc_t r = gf_make_buf(gf_global(static_cast<const W *>(a.send[q])) + blk, bytes);
             return __builtin_bit_cast(V, gf_buf_ld128u<AUX>(r, off));
         };
-        constexpr int U = 8;
+        // Loads in flight per thread.  The big dense sweep runs best with one (measured at P = 8:
+        // 6.6 TB/s against 6.4 with eight; plenty of wavefronts are resident and more requests in
+        // flight only open more DRAM pages at once); the small packed buffer of a CSC plan is
+        // latency-bound (a few dozen workgroups) and wants many.
+        constexpr int U = DENSE ? 1 : 8;
         V v;
         if constexpr (HIER) {
             const int G = a.G;
@@ -158,36 +162,33 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
             HierWalk rd(s, M, G), ap(s, M, G);       // one walks ahead issuing loads, one applies them
             V y = {};
             v = y;
-            int pos = 0;
-            for (; pos + U <= P; pos += U) {
+            // batches of up to U loads in flight; a short last batch keeps all of its loads in
+            // flight too (the count is uniform across the workgroup)
+            for (int pos = 0; pos < P; pos += U) {
+                const int nb = P - pos < U ? P - pos : U;
                 V x[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) { x[u] = ld(rd.rank()); rd.next(); }
+                for (int u = 0; u < U; ++u)
+                    if (u < nb) { x[u] = ld(rd.rank()); rd.next(); }
 #pragma unroll
-                for (int u = 0; u < U; ++u) { hier_feed(v, y, x[u], ap.l, ap.j, G, add); ap.next(); }
-            }
-            for (; pos < P; ++pos) {
-                const V x = ld(ap.rank());
-                hier_feed(v, y, x, ap.l, ap.j, G, add);
-                ap.next();
+                for (int u = 0; u < U; ++u)
+                    if (u < nb) { hier_feed(v, y, x[u], ap.l, ap.j, G, add); ap.next(); }
             }
         } else {
             int q = s;
             v = ld(q);
-            int j = 1;
-            for (; j + U - 1 < P; j += U) {
+            for (int j = 1; j < P; j += U) {
+                const int nb = P - j < U ? P - j : U;
                 V x[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    q = q + 1 == P ? 0 : q + 1;
-                    x[u] = ld(q);
-                }
+                for (int u = 0; u < U; ++u)
+                    if (u < nb) {
+                        q = q + 1 == P ? 0 : q + 1;
+                        x[u] = ld(q);
+                    }
 #pragma unroll
-                for (int u = 0; u < U; ++u) v = hop16(v, x[u]);
-            }
-            for (; j < P; ++j) {
-                q = q + 1 == P ? 0 : q + 1;
-                v = hop16(v, ld(q));
+                for (int u = 0; u < U; ++u)
+                    if (u < nb) v = hop16(v, x[u]);
             }
         }
         gf_buf_st<GF_AUX_CACHED>(__builtin_bit_cast(gf_u32x4, v),

@@ -180,6 +180,90 @@ __global__ __launch_bounds__(SEL_T) void k_select(const float *__restrict__ scor
     }
 }
 
+// The same selection with every thread holding its keys in registers: thread t owns the KPT
+// consecutive chunks [t * KPT, t * KPT + KPT), reads their scores once (128-bit loads), runs the
+// four radix passes on registers, and one scan over the threads' counts places its chunks in the
+// ascending output.  For n_chunks <= 1024 * KPT; the time no longer grows with n_chunks.
+template <int KPT>
+__global__ __launch_bounds__(SEL_T) void k_select_reg(const float *__restrict__ score, int32_t nc, int32_t k,
+                                                      int32_t C, int64_t N,
+                                                      int32_t *__restrict__ sel, uint8_t *__restrict__ mask,
+                                                      int64_t *__restrict__ packed_len, int32_t *__restrict__ slotmap)
+{
+    static_assert(KPT % 4 == 0 && KPT <= 32, "counts of a thread travel in 16 bits");
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wave_tot[SEL_T / 64];
+    __shared__ uint32_t s_bin, s_remaining;
+    const int tid = threadIdx.x;
+    const int base = tid * KPT;
+
+    uint32_t key[KPT];
+    const bool vec = gf_aligned(score, 16);
+#pragma unroll
+    for (int i = 0; i < KPT; i += 4) {
+        const int c = base + i;
+        if (vec && c + 3 < nc) {
+            const gf_f32x4 v = *reinterpret_cast<const gf_f32x4 *>(score + c);
+            key[i] = ord_key(v.x); key[i + 1] = ord_key(v.y); key[i + 2] = ord_key(v.z); key[i + 3] = ord_key(v.w);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) key[i + j] = c + j < nc ? ord_key(score[c + j]) : 0u;
+        }
+    }
+
+    // ---- key of the k-th largest score, one byte per pass
+    uint32_t prefix = 0, decided = 0, remaining = static_cast<uint32_t>(k);
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < KPT; ++i)
+            if (base + i < nc && (key[i] & decided) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
+        __syncthreads();
+        const uint32_t mine = tid < 256 ? hist[255 - tid] : 0u;      // bin 255 - t: the scan counts higher bins
+        uint32_t total;
+        const uint32_t above = block_excl_scan(mine, wave_tot, &total);
+        if (tid < 256 && above < remaining && above + mine >= remaining) {
+            s_bin = static_cast<uint32_t>(255 - tid);
+            s_remaining = remaining - above;
+        }
+        __syncthreads();
+        prefix |= s_bin << shift;
+        decided |= 255u << shift;
+        remaining = s_remaining;
+        __syncthreads();
+    }
+    const uint32_t T = prefix;            // every key above T is taken
+    const uint32_t r = remaining;         // plus the first r chunks whose key equals T
+
+    // ---- ordered compaction: one scan over the threads' counts
+    uint32_t gt = 0, eq = 0;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i)
+        if (base + i < nc) { gt += key[i] > T; eq += key[i] == T; }
+    uint32_t total;
+    const uint32_t ex = block_excl_scan(gt | (eq << 16), wave_tot, &total);
+    uint32_t gt_before = ex & 0xffffu, eq_before = ex >> 16;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        const int c = base + i;
+        if (c < nc) {
+            const bool g = key[i] > T, e = key[i] == T;
+            const bool take = g || (e && eq_before < r);
+            const int32_t rank = static_cast<int32_t>(gt_before + (eq_before < r ? eq_before : r));
+            if (take) sel[rank] = c;
+            if (mask) mask[c] = take ? 1 : 0;
+            if (slotmap) slotmap[c] = take ? rank : -1;
+            if (packed_len && c == nc - 1) {
+                const int64_t last_len = N - static_cast<int64_t>(nc - 1) * C;
+                *packed_len = static_cast<int64_t>(k) * C - (take ? C - last_len : 0);
+            }
+            gt_before += g;
+            eq_before += e;
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" gf_status gf_chunk_score_select(const gf_plan *pl, const float *chunk_l1,
@@ -215,8 +299,16 @@ extern "C" gf_status gf_chunk_score_select(const gf_plan *pl, const float *chunk
     else GF_SCORE(0);
 #undef GF_SCORE
     GF_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_T), 0, st,
-                       scores, nc, k, pl->chunk, pl->N, sel_idx, mask, packed_len, slotmap);
+#define GF_SELECT(K) hipLaunchKernelGGL(k_select_reg<K>, dim3(1), dim3(SEL_T), 0, st, scores, nc, k, pl->chunk, pl->N, \
+                                        sel_idx, mask, packed_len, slotmap)
+    if (nc <= SEL_T * 4) GF_SELECT(4);
+    else if (nc <= SEL_T * 8) GF_SELECT(8);
+    else if (nc <= SEL_T * 16) GF_SELECT(16);
+    else if (nc <= SEL_T * 32) GF_SELECT(32);
+    else
+        hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_T), 0, st,
+                           scores, nc, k, pl->chunk, pl->N, sel_idx, mask, packed_len, slotmap);
+#undef GF_SELECT
     GF_LAUNCH_CHECK();
     return GF_OK;
 }

@@ -105,11 +105,12 @@ def test_pool_beyond_two_to_the_31_elements(gfm):
     assert np.array_equal(pipe.out_pool[tidx].cpu().numpy().view(np.uint32), out.view(np.uint32))
 
 
-@pytest.mark.parametrize("chunk", [4096, 8192, 16384])
+@pytest.mark.parametrize("chunk", [1024, 2048, 4096, 8192, 16384])
 @pytest.mark.parametrize("mode", ["gather", "pool"])
-def test_short_power_of_two_chunks_swept_several_at_a_time(gfm, chunk, mode):
-    """Chunks of 4096 / 8192 / 16384 elements are processed several per workgroup; mixes plain
-    groups with groups that hold tensor borders, an unaligned tensor, and the ragged pool end."""
+def test_power_of_two_chunks_around_the_sub_tile_length(gfm, chunk, mode):
+    """Chunks of 1024 ... 16384 elements (an eighth of a sub-tile, one, two: each launch shape of the
+    sweep); mixes plain chunks with chunks that hold tensor borders, an unaligned tensor, and the
+    ragged pool end."""
     sizes = [chunk * 5, 100, chunk * 2 + 4, 5000, chunk * 9, 7, chunk * 3]
     w = _wl(sizes, 3, chunk, 0.3)
     for schedule in ("lagged", "immediate"):

@@ -242,7 +242,8 @@ def test_cast_rounding_boundaries(gfm):
 # -------------------------------------------------------------------- selection
 
 @pytest.mark.parametrize("nc,k", [(1, 1), (5, 1), (5, 5), (245, 62), (1861, 187), (3120, 32), (50_000, 777),
-                                  (2049, 1024)])
+                                  (2049, 1024), (4096, 4096), (4097, 409), (8192, 1), (8199, 4100), (16384, 163),
+                                  (16385, 16000), (32768, 3277), (32769, 32), (12480, 125)])
 def test_select_bit_exact_including_ties(gfm, nc, k):
     gf, _ = gfm
     rng = np.random.default_rng(nc + k)
@@ -267,6 +268,13 @@ def test_select_bit_exact_including_ties(gfm, nc, k):
     assert np.array_equal(sel.cpu().numpy(), want)
     assert np.array_equal(mask.cpu().numpy(), wmask)
     assert int(plen.item()) == ob.packed_len(nc * C - 3, C, want)
+    # a score vector that is only 4-byte aligned
+    odd = torch.zeros(nc + 1, dtype=torch.float32, device="cuda")
+    sel.fill_(-1)
+    gf.gf_chunk_score_select(plan, d_l1, k=k, scores=odd[1:], sel_idx=sel, workspace=plan.workspace())
+    torch.cuda.synchronize()
+    same_bits(odd[1:], sc, "scores at an odd address")
+    assert np.array_equal(sel.cpu().numpy(), want)
     # all-equal scores: the lowest indices win
     d_l1.fill_(1.0)
     gf.gf_chunk_score_select(plan, d_l1, k=k, sel_idx=sel, workspace=plan.workspace())
