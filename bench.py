@@ -36,10 +36,12 @@ HBM_PEAK_GBS = 8000.0
 # read + bytes written between L2 and the fabric, from the tables under profiles/.  Keyed by
 # (workload, input layout, schedule): a run in any other configuration reports null.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/k_fuse_fused_alexnet_csc.md: FETCH 3 820 996.6 x 2 KiB + WRITE 4 002 746.6 KiB per launch
-    ("alexnet_csc", "gather", "lagged"): 7825400947 + 4098812480,
-    # profiles/kernel_stats_other_workloads.md, cast kernel: FETCH 969 289.3 x 2 KiB + WRITE 952 581.8 KiB
-    ("alexnet_dense", "gather", "dense"): 1985104486 + 975443763,
+    # profiles/k_fuse_fused_resnet50_csc.md: FETCH 6 394 793.4 x 2 KiB + WRITE 6 423 586.0 KiB per launch
+    ("resnet50_csc", "gather", "lagged"): 13096536832 + 6577752064,
+    # profiles/k_fuse_fused_alexnet_csc.md: FETCH 3 813 208.7 x 2 KiB + WRITE 4 002 746.6 KiB per launch
+    ("alexnet_csc", "gather", "lagged"): 7809451392 + 4098812488,
+    # profiles/kernel_stats_other_workloads.md, cast kernel: FETCH 954 000.3 x 2 KiB + WRITE 952 581.8 KiB
+    ("alexnet_dense", "gather", "dense"): 1953792563 + 975443712,
 }
 
 DEFAULT_WORKLOAD = "resnet50_csc"     # the largest single-GPU configuration of the five
@@ -262,6 +264,56 @@ def run_overlap(name: str, steps: int, warmup: int, n_streams: int = 2):
     return res
 
 
+def run_overlap_csc(name: str, steps: int, warmup: int, n_ranges: int = 8, buckets: int = 4):
+    """A sparse workload swept range by range (n_ranges equal chunk ranges in generation order) with
+    the packed buffer reduced and unpacked bucket by bucket (theta = a quarter of it) on a second
+    stream while the next ranges are swept: Section 3.2's enable-overlap setting, with no backward
+    to overlap with here, so this shows what issuing range by range costs against the single pass."""
+    import torch
+    from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
+
+    w = wl.config(name)
+    torch.cuda.set_device(0)
+    plan = gf.Plan(w.sizes, 1 << 60, w.chunk, w.P, to_device=False)
+    nc = plan.n_chunks
+    plan.close()
+    k = w.k_for(nc)
+    theta = max(1, k // buckets) * w.chunk - 1          # a bucket closes every k / buckets packed chunks
+    bounds = sorted({max(1, (r + 1) * nc // n_ranges) for r in range(n_ranges)} | {nc})
+    ov = pl.OverlappedCsc(w.sizes, w.P, w.chunk, theta, w.loss_scale, k, bounds, mu=w.mu, wire=w.wire)
+    n_sets = 3
+    tables, keep = resident_gradient_sets(w, n_sets, "gather")
+    it = 0
+    for _ in range(warmup):
+        ov.pipe.use_tables(*tables[it % n_sets]); ov.step(); it += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ov.pipe.use_tables(*tables[it % n_sets]); ov.step(); it += 1
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    L = int(ov.pipe.packed_len.item())
+    total, _ = algorithmic_bytes(w, L, "lagged")
+    graphs = []
+    for s in range(n_sets):                              # one recorded iteration per resident gradient set
+        ov.pipe.use_tables(*tables[s]); graphs.append(ov.capture())
+    for s in range(n_sets):
+        graphs[s].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graphs[it % n_sets].replay(); it += 1
+    torch.cuda.synchronize()
+    ms_graph = (time.perf_counter() - t0) * 1e3 / steps
+    res = {"P": w.P, "N": w.N, "chunk_ranges": len(bounds), "packed_buckets": -(-k // max(1, k // buckets)),
+           "ms_per_step": ms, "gbs": total / ms / 1e6, "bytes_per_step": total,
+           "frac_of_hbm_peak": total / ms / 1e6 / HBM_PEAK_GBS,
+           "ms_per_step_as_graph": ms_graph, "gbs_as_graph": total / ms_graph / 1e6}
+    del ov, tables, keep
+    torch.cuda.empty_cache()
+    return res
+
+
 def cpu_baseline(name: str, schedule: str, threads: int):
     """The CPU checker, as it stands, on host cores: whole steady-state iterations of the same
     workload with the worker count cut down so that the run stays bounded.  Timed twice on the
@@ -390,6 +442,8 @@ def main() -> int:
     if a.ladder and not a.pmc_probe:
         for nm in ("alexnet_dense", "resnet50_dense_4mb", "resnet50_pertensor_fp16"):
             others[nm + "+buckets_on_side_streams"] = run_overlap(nm, 10, 5, 4)
+        for nm in ("alexnet_csc", "resnet50_csc"):
+            others[nm + "+ranges_and_buckets_as_they_fill"] = run_overlap_csc(nm, 10, 5)
     if w.chunk and not a.pmc_probe and a.others:
         # the same workload with Algorithm 1's SGD-update step fused into the unpack
         r = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, sgd=(0.9, -0.01))
