@@ -18,10 +18,14 @@
  * sums and against the traffic formula of Section 2.4; the hierarchical
  * allreduce, message by message, against its formula, hand-worked fp16 sums
  * that tell the chain and rotation orders apart, exact integer sums and the
- * message size of Section 2.4; selection against a
- * full sort; residual bookkeeping against the conservation property stated
- * with Algorithm 1.  End-to-end numeric values: PARITY UNPINNED by the paper
- * (it prints no worked example); they rest on the pins above.
+ * message size of Section 2.4; selection against a full sort (scores that are
+ * not numbers included); pack, cast, unpack and the SGD update on both wire
+ * types against numpy's fp32 / fp16 arithmetic element by element; residual
+ * bookkeeping against the conservation property stated with Algorithm 1 on
+ * both wire types; the warm-up chunk counts against hand-worked values.  The
+ * same pins run once more against a build of this file under AddressSanitizer
+ * and UndefinedBehaviorSanitizer.  End-to-end numeric values: PARITY UNPINNED
+ * by the paper (it prints no worked example); they rest on the pins above.
  *
  * The only parallelism is an OpenMP loop over workers (or over disjoint
  * element ranges of the ring), which changes no arithmetic and no order
