@@ -125,7 +125,10 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
     int64_t seg_lo = static_cast<int64_t>(s) * seg; if (seg_lo > Lb) seg_lo = Lb;
     int64_t seg_hi = seg_lo + seg; if (seg_hi > Lb) seg_hi = Lb;
     seg_lo += lo; seg_hi += lo;
-    const int64_t e = seg_lo + (static_cast<int64_t>(bis) * GF_RING_GROUPS_PER_BLOCK + threadIdx.x) * A;
+    // 16-byte groups per workgroup = its thread count (fewer than the full 512 when a small
+    // packed buffer would otherwise leave most of the chip idle)
+    const int gpb = DENSE ? GF_RING_GROUPS_PER_BLOCK : static_cast<int>(blockDim.x);
+    const int64_t e = seg_lo + (static_cast<int64_t>(bis) * gpb + threadIdx.x) * A;
     if (e >= seg_hi) return;
     const int n = seg_hi - e < A ? static_cast<int>(seg_hi - e) : A;
 
@@ -141,10 +144,9 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
         // Buffer descriptors anchored at this workgroup's first element: the base is uniform,
         // each lane adds 16 bytes times its index, and nothing past the segment is reachable.
         constexpr int AUX = DENSE ? GF_AUX_STREAM : GF_AUX_CACHED;
-        const int64_t blk = seg_lo + static_cast<int64_t>(bis) * GF_RING_GROUPS_PER_BLOCK * A;
+        const int64_t blk = seg_lo + static_cast<int64_t>(bis) * gpb * A;
         const int64_t left = (seg_hi - blk) * static_cast<int64_t>(sizeof(W));
-        const uint32_t bytes = left < GF_RING_GROUPS_PER_BLOCK * 16 ? static_cast<uint32_t>(left)
-                                                                    : GF_RING_GROUPS_PER_BLOCK * 16u;
+        const uint32_t bytes = left < gpb * 16 ? static_cast<uint32_t>(left) : static_cast<uint32_t>(gpb) * 16u;
         const int off = threadIdx.x * 16;
         auto ld = [&](int q) {
             const __amdgpu_buffer_rsrc_t r = gf_make_buf(gf_global(static_cast<const W *>(a.send[q])) + blk, bytes);
@@ -154,7 +156,7 @@ __global__ __launch_bounds__(GF_RING_GROUPS_PER_BLOCK) void k_ring(const RingArg
         // 6.6 TB/s against 6.4 with eight; plenty of wavefronts are resident and more requests in
         // flight only open more DRAM pages at once); the small packed buffer of a CSC plan is
         // latency-bound (a few dozen workgroups) and wants many.
-        constexpr int U = DENSE ? 1 : 8;
+        constexpr int U = DENSE ? 1 : 16;
         V v;
         if constexpr (HIER) {
             const int G = a.G;
@@ -280,8 +282,14 @@ gf_status ring_reduce(const gf_plan *pl, const void *const *sendbuf, int64_t L, 
         const int64_t n_buckets = (L + span - 1) / span;
         const int64_t seg = gf_ring_segment_len(full, pl->ring_M, pl->wire);
         const int64_t groups = seg / A;
-        const int64_t bps = (groups + GF_RING_GROUPS_PER_BLOCK - 1) / GF_RING_GROUPS_PER_BLOCK;
+        // a small packed buffer is cut into smaller workgroups (down to one wavefront) until a
+        // thousand of them exist: with 64 workgroups of 512 threads each CU's own load bandwidth
+        // bounds the kernel (measured at P = 64, 0.5 MB per worker)
+        int64_t gpb = GF_RING_GROUPS_PER_BLOCK;
+        while (gpb > 64 && (groups + gpb - 1) / gpb * pl->ring_M * n_buckets < 1024) gpb /= 2;
+        const int64_t bps = (groups + gpb - 1) / gpb;
         if (bps * pl->ring_M * n_buckets > (int64_t{1} << 30)) return GF_EINVAL;
+        const dim3 block(static_cast<unsigned>(gpb));
         a.blocks_per_segment = static_cast<int32_t>(bps);
         a.bucket_span = span;
         a.chunks_per_bucket = static_cast<int32_t>(span / pl->chunk);

@@ -59,15 +59,16 @@ __global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1
             return static_cast<float>(n);
         }
     };
-    // eight workers' loads are in flight at a time
+    // several workers' loads are in flight at a time; the additions keep the order of the workers
+    constexpr int B = SUBS <= 1 ? 16 : 8;
     double s = 0.0;
     int p = 0;
-    for (; p + 8 <= P; p += 8) {
-        float x[8];
+    for (; p + B <= P; p += B) {
+        float x[B];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = norm(p + u);
+        for (int u = 0; u < B; ++u) x[u] = norm(p + u);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += static_cast<double>(x[u]);
+        for (int u = 0; u < B; ++u) s += static_cast<double>(x[u]);
     }
     for (; p < P; ++p) s += static_cast<double>(norm(p));
     score[c] = static_cast<float>(s);
@@ -213,24 +214,35 @@ __global__ __launch_bounds__(SEL_T) void k_select_reg(const float *__restrict__ 
 
     // ---- key of the k-th largest score, one byte per pass
     uint32_t prefix = 0, decided = 0, remaining = static_cast<uint32_t>(k);
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
     for (int shift = 24; shift >= 0; shift -= 8) {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
 #pragma unroll
         for (int i = 0; i < KPT; ++i)
             if (base + i < nc && (key[i] & decided) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
         __syncthreads();
-        const uint32_t mine = tid < 256 ? hist[255 - tid] : 0u;      // bin 255 - t: the scan counts higher bins
-        uint32_t total;
-        const uint32_t above = block_excl_scan(mine, wave_tot, &total);
-        if (tid < 256 && above < remaining && above + mine >= remaining) {
-            s_bin = static_cast<uint32_t>(255 - tid);
-            s_remaining = remaining - above;
+        if (tid < 64) {
+            // The first wavefront finds the bin of the remaining-th largest key on its own: lane l
+            // holds bins 255 - 4l ... 252 - 4l (highest first), a scan over the lanes counts the keys
+            // in higher bins.
+            uint32_t cnt[4], four = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { cnt[j] = hist[255 - 4 * tid - j]; four += cnt[j]; }
+            uint32_t above = wave_incl_scan(four) - four;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (above < remaining && above + cnt[j] >= remaining) {
+                    s_bin = static_cast<uint32_t>(255 - 4 * tid - j);
+                    s_remaining = remaining - above;
+                }
+                above += cnt[j];
+            }
         }
         __syncthreads();
         prefix |= s_bin << shift;
         decided |= 255u << shift;
         remaining = s_remaining;
+        if (tid < 256) hist[tid] = 0;                                // for the next pass
         __syncthreads();
     }
     const uint32_t T = prefix;            // every key above T is taken
