@@ -235,3 +235,59 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert status(gf.gf_unpack_sgd_update, csc, fake, 1025, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake, **upd) == E
     assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake, **upd) == S
     assert status(gf.gf_unpack_sgd_update, dense, fake, 8192, w_tensors=fake, hu_tensors=fake, **upd) == S
+
+
+def test_modifier_bits_and_range_calls_validate_before_touching_the_gpu():
+    csc = gf.Plan([4096, 4096], 1 << 40, 1024, 2, to_device=False)        # 8 chunks
+    dense = gf.Plan([4096, 4096], 1 << 40, 0, 2, to_device=False)
+    fake, ws = 0x1000, 0x100
+    E, S, Lim = gf.GF_EINVAL, gf.GF_ESTATE, gf.GF_ELIMIT
+    A, K, SL, DF = gf.GF_PHASE_ACCUM, gf.GF_PHASE_PACK, gf.GF_PHASE_SLOTS, gf.GF_PHASE_DEFER_NORMS
+
+    def status(fn, *a, **kw):
+        with pytest.raises(gf.GfError) as e:
+            fn(*a, stream=0, **kw)
+        return e.value.status
+
+    sparse = dict(pools=fake, residual=fake, sel_idx=fake, k=2, sendbuf=fake)
+    # modifier bits need what they modify
+    assert status(gf.gf_fuse_pack, csc, SL, **sparse, workspace=ws) == E                 # no phase at all
+    assert status(gf.gf_fuse_pack, csc, 16 | A, pools=fake, residual=fake, workspace=ws) == E   # unknown bit
+    assert status(gf.gf_fuse_pack, csc, A | SL, pools=fake, residual=fake, workspace=ws) == E   # slots without a pack
+    assert status(gf.gf_fuse_pack, csc, A | K | SL, pools=fake, residual=fake, sendbuf=fake, workspace=ws) == E  # no selection
+    assert status(gf.gf_fuse_pack, csc, K | DF, residual=fake, sel_idx=fake, k=2, sendbuf=fake, workspace=ws) == E  # no norms in a pack
+    assert status(gf.gf_fuse_pack, dense, A | K | DF, pools=fake, sendbuf=fake, workspace=ws) == E
+    assert status(gf.gf_fuse_pack, csc, A | DF, pools=fake, residual=fake) == E               # nowhere to leave them
+    assert status(gf.gf_fuse_pack, csc, A | K | SL | DF, **sparse, workspace=ws) == S         # valid, not uploaded
+    assert status(gf.gf_fuse_pack, csc, A | DF, pools=fake, residual=fake, workspace=ws) == S
+    # a selection that takes its norms from the workspace needs one
+    assert status(gf.gf_chunk_score_select, csc, None, k=1, sel_idx=fake, scores=fake) == E
+    assert status(gf.gf_chunk_score_select, csc, None, k=1, sel_idx=fake, scores=fake, workspace=0x104) == E
+    assert status(gf.gf_chunk_score_select, csc, None, k=1, sel_idx=fake, workspace=ws) == S
+    # chunk ranges
+    rng = dict(pools=fake, residual=fake, workspace=ws)
+    assert status(gf.gf_fuse_pack_range, csc, A, -1, 4, **rng) == E
+    assert status(gf.gf_fuse_pack_range, csc, A, 5, 4, **rng) == E
+    assert status(gf.gf_fuse_pack_range, csc, A, 0, 9, **rng) == E
+    assert status(gf.gf_fuse_pack_range, dense, A | K, 0, 1, pools=fake, sendbuf=fake) == E      # chunks needed
+    assert status(gf.gf_fuse_pack_range, csc, K, 2, 4, residual=fake, sel_idx=fake, k=2, sendbuf=fake, workspace=ws) == E
+    assert status(gf.gf_fuse_pack_range, csc, A | K, 2, 4, **sparse, workspace=ws) == S
+    assert status(gf.gf_ring_reduce_range, csc, fake, 2048, fake, None, 2, 0, 4) == E              # no selection
+    assert status(gf.gf_ring_reduce_range, csc, fake, 2000, fake, fake, 2, 0, 4) == E              # L is the capacity k*C
+    assert status(gf.gf_ring_reduce_range, csc, fake, 2048, fake, fake, 2, 3, 2) == E
+    assert status(gf.gf_ring_reduce_range, csc, fake, 2048, fake, fake, 9, 0, 4) == E
+    assert status(gf.gf_ring_reduce_range, dense, fake, 8192, fake, fake, 1, 0, 1) == E
+    assert status(gf.gf_ring_reduce_range, csc, fake, 2048, fake, fake, 2, 0, 4) == S
+    assert status(gf.gf_unpack_range, csc, fake, 2048, None, 2, 0, 4, out_pool=fake) == E
+    assert status(gf.gf_unpack_range, csc, fake, 2048, fake, 2, 0, 9, out_pool=fake) == E
+    assert status(gf.gf_unpack_range, csc, fake, 2048, fake, 2, 0, 4) == E                         # nowhere to write
+    assert status(gf.gf_unpack_range, dense, fake, 8192, fake, 1, 0, 1, out_pool=fake) == E
+    assert status(gf.gf_unpack_range, csc, fake, 2048, fake, 2, 0, 4, out_pool=fake) == S
+    gf.gf_ring_reduce_range(csc, fake, 2048, fake, fake, 2, 3, 3, stream=0)                        # empty range: nothing to do
+    gf.gf_unpack_range(csc, fake, 2048, fake, 2, 3, 3, out_pool=fake, stream=0)
+    # the variant with its own scratch takes neither hand-over and has a size limit
+    assert status(gf.gf_fuse_pack_static, csc, A | K | SL, **sparse) == E
+    assert status(gf.gf_fuse_pack_static, csc, A | DF, pools=fake, residual=fake) == E
+    big = gf.Plan([5000 * 8200], 1 << 40, 8200, 64, to_device=False)
+    assert big.workspace_bytes() > gf.GF_STATIC_SCRATCH_BYTES
+    assert status(gf.gf_fuse_pack_static, big, A, pools=fake, residual=fake, chunk_l1=fake) == Lim
