@@ -342,8 +342,19 @@ void k_fuse(const FuseArgs a)
     f.pool_p = HAS_G ? static_cast<const GT *>(a.tab[static_cast<int64_t>(p) * a.tab_stride]) : nullptr;
     f.us = gf_unit_src{0, -1, 0};
     if constexpr (HAS_G) f.us = a.unit_src[static_cast<int64_t>(tile) * a.subs + sub];
-    if constexpr (MODE == MODE_FUSED || MODE == MODE_SCALE) {
-        if (a.slotmap) slot = slot_read;
+    {
+        // All of the above are scalar loads that return together.  Naming every result here, in
+        // one place, keeps the compiler from waiting for the first of them (the slot, which
+        // decides a branch) before it has issued the others.
+        uint64_t r0 = reinterpret_cast<uint64_t>(f.res_p), s0 = reinterpret_cast<uint64_t>(f.snd_p);
+        uint64_t p0 = reinterpret_cast<uint64_t>(f.pool_p), o0 = static_cast<uint64_t>(f.us.src_off);
+        int32_t t0 = f.us.tensor, sl = slot_read;
+        asm volatile("" : "+s"(r0), "+s"(s0), "+s"(p0), "+s"(o0), "+s"(t0), "+s"(sl));
+        f.res_p = reinterpret_cast<float *>(r0); f.snd_p = reinterpret_cast<void *>(s0);
+        f.pool_p = reinterpret_cast<const GT *>(p0); f.us.src_off = static_cast<int64_t>(o0); f.us.tensor = t0;
+        if constexpr (MODE == MODE_FUSED || MODE == MODE_SCALE) {
+            if (a.slotmap) slot = sl;
+        }
     }
     const int64_t left = a.N - static_cast<int64_t>(tile) * a.tile;
     const int tile_len = left < a.tile ? static_cast<int>(left) : a.tile;
