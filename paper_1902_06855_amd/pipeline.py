@@ -336,11 +336,12 @@ class OverlappedCsc:
 
     def __init__(self, sizes: Sequence[int], P: int, chunk: int, theta: int, loss_scale: float, k: int,
                  boundaries: Sequence[int], mu: float = 1.0, wire: str = "f16", device: str = "cuda",
-                 grad: str = "f32", groups: int = 0, scatter_out: bool = False):
+                 grad: str = "f32", groups: int = 0, scatter_out: bool = False, allgather: bool = False):
         if not chunk:
             raise ValueError("a plan with chunks is needed (dense plans: OverlappedDense)")
         self.pipe = Pipeline(sizes, P, chunk, theta, loss_scale, k=k, mu=mu, wire=wire, schedule="lagged",
-                             scatter_out=scatter_out, device=device, grad=grad, groups=groups, fast=True)
+                             scatter_out=scatter_out, allgather=allgather, device=device, grad=grad, groups=groups,
+                             fast=True)
         nc = self.pipe.n_chunks
         self.bounds = [int(b) for b in boundaries]
         if not self.bounds or self.bounds != sorted(set(self.bounds)) or self.bounds[0] < 1 or self.bounds[-1] != nc:

@@ -37,7 +37,8 @@ def pools_of(w, t):
 
 
 def check_iteration(ov, w, st, pools, k, theta, groups, what):
-    """One checker iteration on the same gradients; compares everything the GPU left behind."""
+    """One checker iteration on the same gradients; compares everything the GPU left behind
+    (also the all-gather copies and the per-tensor outputs when the pipeline keeps them)."""
     p = ov.pipe
     out = np.full(w.N, np.float32(-6.0))
     r = op.csc_iteration(st, pools, w.chunk, k, w.loss_scale, w.mu, "lagged", w.wire, out=out, theta=theta,
@@ -51,6 +52,16 @@ def check_iteration(ov, w, st, pools, k, theta, groups, what):
     same(p.reduced[:L].view(it), r["reduced"].view(nt), f"{what} reduced")
     same(p.out_pool, out, f"{what} out")
     assert np.array_equal(p.sel.cpu().numpy()[:k], r["sel_next"]), f"{what} selection"
+    if p.ag is not None:
+        for q in (0, w.P - 1):
+            same(p.ag[q][:L].view(it), r["reduced"].view(nt), f"{what} all-gather copy of rank {q}")
+    if p.out_tensors is not None:
+        written = np.zeros(w.N, dtype=bool)
+        for c in r["sel"]:
+            written[c * w.chunk:(c + 1) * w.chunk] = True
+        for j, (v, m) in enumerate(zip(op.views(out, w.sizes), op.views(written, w.sizes))):
+            got = p.out_tensors[j].cpu().numpy()
+            assert np.array_equal(bits(got[m]), bits(np.ascontiguousarray(v[m]))), f"{what} out tensor {j}"
     return r
 
 
@@ -74,7 +85,8 @@ def test_range_by_range_iterations_equal_the_checker(gfm, case, wire, mode):
         nc = ob.n_chunks(w.N, C)
         k = w.k_for(nc)
         bounds = sorted(set(max(1, int(f * nc)) for f in fracs) | {nc})
-        ov = pl.OverlappedCsc(w.sizes, P, C, theta, w.loss_scale, k, bounds, mu=w.mu, wire=wire, groups=groups)
+        ov = pl.OverlappedCsc(w.sizes, P, C, theta, w.loss_scale, k, bounds, mu=w.mu, wire=wire, groups=groups,
+                              scatter_out=theta_chunks == 2, allgather=theta_chunks == 0)
         st = op.new_state(P, w.N)
         for t in range(4):
             g, pools = pools_of(w, t)

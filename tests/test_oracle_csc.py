@@ -322,8 +322,9 @@ def test_csc_iteration_reduces_each_packed_bucket_on_its_own_ring():
 
 # ------------------------------- packing and reducing while the pool is still filling
 
+@pytest.mark.parametrize("wire,groups", [("f16", 0), ("f32", 0), ("f16", 3)])
 @pytest.mark.parametrize("theta", [0, 3 * 64, 1 << 40])
-def test_sweeping_the_pool_range_by_range_changes_nothing(theta):
+def test_sweeping_the_pool_range_by_range_changes_nothing(theta, wire, groups):
     """Section 3.2 with the enable-overlap setting: important chunks are packed as they fill and a
     bucket of the buffer is allreduced as soon as more than theta is waiting.  However the pool
     is cut into ranges, every byte equals the iteration that sweeps the pool in one go."""
@@ -332,16 +333,16 @@ def test_sweeping_the_pool_range_by_range_changes_nothing(theta):
     nc = ob.n_chunks(w.N, w.chunk)
     k = w.k_for(nc)
     ref = op.new_state(w.P, w.N)
-    op.csc_iteration(ref, _pools(w, 0), w.chunk, k, w.loss_scale, 0.9, "lagged", theta=theta)
+    op.csc_iteration(ref, _pools(w, 0), w.chunk, k, w.loss_scale, 0.9, "lagged", wire, theta=theta, groups=groups)
     rng = np.random.default_rng(5)
     cuts = [[nc], list(range(1, nc + 1)), [nc // 2, nc], [1, nc - 1, nc]]
     cuts += [sorted(set(rng.choice(np.arange(1, nc), size=5, replace=False).tolist() + [nc])) for _ in range(4)]
     for t in (1, 2):
         pools = _pools(w, t)
         states = [copy.deepcopy(ref) for _ in cuts]
-        want = op.csc_iteration(ref, pools, w.chunk, k, w.loss_scale, 0.9, "lagged", theta=theta)
+        want = op.csc_iteration(ref, pools, w.chunk, k, w.loss_scale, 0.9, "lagged", wire, theta=theta, groups=groups)
         for st, cut in zip(states, cuts):
-            got = op.csc_iteration_in_ranges(st, pools, w.chunk, k, w.loss_scale, 0.9, cut, theta)
+            got = op.csc_iteration_in_ranges(st, pools, w.chunk, k, w.loss_scale, 0.9, cut, theta, wire, groups=groups)
             for name in ("acc", "l1", "send", "hg", "reduced", "out", "red_l1", "score_post", "sel_next"):
                 assert np.array_equal(got[name], want[name]), (name, cut, t)
             assert np.array_equal(st.hg, ref.hg) and np.array_equal(st.sel, ref.sel)
