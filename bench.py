@@ -323,7 +323,7 @@ def cpu_baseline(name: str, schedule: str, threads: int):
     from paper_1902_06855_amd import workloads as wl
 
     w = wl.config(name)
-    P_s = min(w.P, 8)                      # sample: the first P_s workers, every tensor, full size
+    P_s = min(w.P, 16)                     # sample: the first P_s workers, every tensor, full size
     ws = wl.Workload(w.name + "_sample", w.sizes, P_s, w.chunk, w.density, w.loss_scale, w.theta,
                      w.iterations, w.mu, w.seed, w.wire)
     sig = wl.sigma_table(w)[:, :P_s]
@@ -333,7 +333,7 @@ def cpu_baseline(name: str, schedule: str, threads: int):
         pools.append(np.stack([op.fuse(row, w.sizes) for row in g]))
         del g
 
-    TIMED = 3                              # steady-state iterations per timing, averaged
+    TIMED = 5                              # steady-state iterations per timing, averaged
 
     def once(nthreads):
         ob.set_threads(nthreads)
