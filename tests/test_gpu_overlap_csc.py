@@ -222,3 +222,37 @@ def test_range_calls_without_the_hand_overs_tile_to_the_whole_call(gfm):
         with pytest.raises(gf.GfError):
             gf.gf_fuse_pack_range(plan, gf.GF_PHASE_ACCUM, 0, nc + 1, pools=gf.ptr_table(pools), residual=gf.ptr_table(hg0))
         plan.close()
+
+
+@pytest.mark.parametrize("name", ["alexnet_csc", "resnet50_csc"])
+def test_full_size_range_by_range_equals_the_single_sweep(gfm, name):
+    """The two sparse configurations at full size, in the shape the benchmark's piecewise row runs
+    (8 chunk ranges, the packed buffer in 4-5 buckets): every buffer the range-by-range driver leaves
+    behind equals, bit for bit, what the single-sweep pipeline leaves (which the full-size test holds
+    against the checker on sampled chunks)."""
+    gf, pl = gfm
+    w = wl.config(name)
+    nc = ob.n_chunks(w.N, w.chunk)
+    k = w.k_for(nc)
+    theta = max(1, k // 4) * w.chunk - 1
+    bounds = sorted({max(1, (r + 1) * nc // 8) for r in range(8)} | {nc})
+    sig = wl.sigma_table(w)
+    one = pl.Pipeline(w.sizes, w.P, w.chunk, theta, w.loss_scale, k=k, mu=w.mu, schedule="lagged")
+    ov = pl.OverlappedCsc(w.sizes, w.P, w.chunk, theta, w.loss_scale, k, bounds, mu=w.mu)
+    for t in range(3):
+        g = wl.gradients(w, t, device="cuda", sig=sig)
+        one.set_gradients(g); ov.pipe.set_gradients(g)
+        one.out_pool.fill_(-1.0); ov.pipe.out_pool.fill_(-1.0)
+        one.step(); ov.step()
+        torch.cuda.synchronize()
+        a, b = one, ov.pipe
+        assert torch.equal(a.sel, b.sel) and torch.equal(a.packed_len, b.packed_len), f"t={t} selection"
+        L = int(a.packed_len.item())
+        assert torch.equal(a.reduced[:L].view(torch.int16), b.reduced[:L].view(torch.int16)), f"t={t} reduced"
+        assert torch.equal(a.out_pool.view(torch.int32), b.out_pool.view(torch.int32)), f"t={t} out"
+        assert torch.equal(a.scores.view(torch.int32), b.scores.view(torch.int32)), f"t={t} scores"
+        for p in range(w.P):
+            assert torch.equal(a.residual[p].view(torch.int32), b.residual[p].view(torch.int32)), f"t={t} hg[{p}]"
+            assert torch.equal(a.send[p][:L].view(torch.int16), b.send[p][:L].view(torch.int16)), f"t={t} send[{p}]"
+        del g
+    assert not torch.all(one.out_pool == -1.0)
