@@ -5,6 +5,7 @@ lagged schedule).  The CPU checker cannot replay 10^9 elements in a test, so:
   * sampled chunks / elements are recomputed by the checker from the same
     gradient bits (copied from the GPU, never regenerated) and compared to the
     bit, through every stage and two iterations (bootstrap + steady state);
+  * the largest configuration is also compared on every element, once;
   * whole small vectors (chunk norms -> scores -> selection) are checked by
     properties that hold at any size: scores are the checker's function of the
     norm vector, the selected set is the checker's top-k of the score vector,
@@ -14,7 +15,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import binding as ob
+from oracle import binding as ob, pipeline as op
 from paper_1902_06855_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -270,3 +271,41 @@ def test_csc_full_size_sampled(mods, name, groups):
     sel2 = pipe.sel.cpu().numpy().copy()
     assert np.array_equal(sel2, ob.select(sc, k)[0]), "selection is the checker's top-k of the scores"
     assert np.array_equal(np.flatnonzero(pipe.mask.cpu().numpy()), sel2)
+
+
+def test_resnet50_csc_full_size_every_element(mods):
+    """The largest configuration (P = 64, 161 scattered tensors per worker, 3120 chunks) compared with
+    the checker on every element, not a sample: the two-pass first iteration and one steady-state
+    iteration in the benchmark's launch configuration.  About 30 GB of host memory."""
+    gf, pl = mods
+    w = wl.config("resnet50_csc")
+    P, N, C = w.P, w.N, w.chunk
+    nc = ob.n_chunks(N, C)
+    k = w.k_for(nc)
+    sig = wl.sigma_table(w)
+    pipe = pl.Pipeline(w.sizes, P, C, w.theta, w.loss_scale, k=k, mu=w.mu, schedule="lagged")
+    st = op.new_state(P, N)
+    pools = np.empty((P, N), dtype=np.float32)
+    for t in range(2):
+        g = wl.gradients(w, t, device="cuda", sig=sig)
+        for p in range(P):                                            # the same bits, copied
+            pools[p] = pool_of(g[p]).cpu().numpy()
+        pipe.set_gradients(g)
+        pipe.out_pool.fill_(-3.0)
+        pipe.step()
+        torch.cuda.synchronize()
+        out = np.full(N, np.float32(-3.0))
+        r = op.csc_iteration(st, pools, C, k, w.loss_scale, w.mu, "lagged", out=out)
+        r.pop("acc")
+        assert np.array_equal(pipe.sel.cpu().numpy(), r["sel_next"]), f"t={t} selection"
+        L = r["send"].shape[1]
+        assert int(pipe.packed_len.item()) == ob.packed_len(N, C, r["sel_next"])
+        assert np.array_equal(u16(pipe.reduced[:L].cpu().numpy()), r["reduced"]), f"t={t} reduced"
+        assert np.array_equal(u32(pipe.out_pool.cpu().numpy()), u32(out)), f"t={t} out"
+        assert np.array_equal(u32(pipe.scores.cpu().numpy()), u32(r["score_post"])), f"t={t} scores"
+        for p in range(P):
+            assert np.array_equal(u16(pipe.send[p][:L].cpu().numpy()), r["send"][p]), f"t={t} send[{p}]"
+            want = torch.from_numpy(st.hg[p]).cuda()
+            assert torch.equal(pipe.residual[p].view(torch.int32), want.view(torch.int32)), f"t={t} hg[{p}]"
+            del want
+        del g, r
