@@ -273,20 +273,22 @@ def test_csc_full_size_sampled(mods, name, groups):
     assert np.array_equal(np.flatnonzero(pipe.mask.cpu().numpy()), sel2)
 
 
-def test_resnet50_csc_full_size_every_element(mods):
-    """The largest configuration (P = 64, 161 scattered tensors per worker, 3120 chunks) compared with
-    the checker on every element, not a sample: the two-pass first iteration and one steady-state
-    iteration in the benchmark's launch configuration.  About 30 GB of host memory."""
+@pytest.mark.parametrize("name", ["resnet50_csc", "alexnet_csc", "resnet50_csc_c4096", "resnet50_csc_c2048",
+                                  "alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb"])
+def test_full_size_every_element(mods, name):
+    """Every measured configuration compared with the checker on every element, not a sample, in
+    the benchmark's launch configuration: for the sparse ones the two-pass first iteration and one
+    steady-state iteration.  The largest (P = 64, 161 scattered tensors per worker, 3120 chunks)
+    takes about 30 GB of host memory."""
     gf, pl = mods
-    w = wl.config("resnet50_csc")
+    w = wl.config(name)
     P, N, C = w.P, w.N, w.chunk
-    nc = ob.n_chunks(N, C)
-    k = w.k_for(nc)
+    k = w.k_for(ob.n_chunks(N, C)) if C else 0
     sig = wl.sigma_table(w)
-    pipe = pl.Pipeline(w.sizes, P, C, w.theta, w.loss_scale, k=k, mu=w.mu, schedule="lagged")
-    st = op.new_state(P, N)
+    pipe = pl.Pipeline(w.sizes, P, C, w.theta, w.loss_scale, k=k, mu=w.mu, wire=w.wire, schedule="lagged")
+    st = op.new_state(P, N) if C else None
     pools = np.empty((P, N), dtype=np.float32)
-    for t in range(2):
+    for t in range(2 if C else 1):
         g = wl.gradients(w, t, device="cuda", sig=sig)
         for p in range(P):                                            # the same bits, copied
             pools[p] = pool_of(g[p]).cpu().numpy()
@@ -294,18 +296,23 @@ def test_resnet50_csc_full_size_every_element(mods):
         pipe.out_pool.fill_(-3.0)
         pipe.step()
         torch.cuda.synchronize()
-        out = np.full(N, np.float32(-3.0))
-        r = op.csc_iteration(st, pools, C, k, w.loss_scale, w.mu, "lagged", out=out)
-        r.pop("acc")
-        assert np.array_equal(pipe.sel.cpu().numpy(), r["sel_next"]), f"t={t} selection"
-        L = r["send"].shape[1]
-        assert int(pipe.packed_len.item()) == ob.packed_len(N, C, r["sel_next"])
-        assert np.array_equal(u16(pipe.reduced[:L].cpu().numpy()), r["reduced"]), f"t={t} reduced"
+        if C:
+            out = np.full(N, np.float32(-3.0))
+            r = op.csc_iteration(st, pools, C, k, w.loss_scale, w.mu, "lagged", w.wire, out=out, theta=w.theta)
+            r.pop("acc")
+            assert np.array_equal(pipe.sel.cpu().numpy(), r["sel_next"]), f"t={t} selection"
+            L = r["send"].shape[1]
+            assert int(pipe.packed_len.item()) == ob.packed_len(N, C, r["sel_next"])
+            assert np.array_equal(u32(pipe.scores.cpu().numpy()), u32(r["score_post"])), f"t={t} scores"
+        else:
+            r = op.dense_iteration(pools, w.sizes, w.theta, w.loss_scale, w.wire)
+            out, L = r["out"], N
+        assert np.array_equal(u16(pipe.reduced[:L].cpu().numpy()), u16(r["reduced"])), f"t={t} reduced"
         assert np.array_equal(u32(pipe.out_pool.cpu().numpy()), u32(out)), f"t={t} out"
-        assert np.array_equal(u32(pipe.scores.cpu().numpy()), u32(r["score_post"])), f"t={t} scores"
         for p in range(P):
-            assert np.array_equal(u16(pipe.send[p][:L].cpu().numpy()), r["send"][p]), f"t={t} send[{p}]"
-            want = torch.from_numpy(st.hg[p]).cuda()
-            assert torch.equal(pipe.residual[p].view(torch.int32), want.view(torch.int32)), f"t={t} hg[{p}]"
-            del want
+            assert np.array_equal(u16(pipe.send[p][:L].cpu().numpy()), u16(r["send"][p])), f"t={t} send[{p}]"
+            if C:
+                want = torch.from_numpy(st.hg[p]).cuda()
+                assert torch.equal(pipe.residual[p].view(torch.int32), want.view(torch.int32)), f"t={t} hg[{p}]"
+                del want
         del g, r
