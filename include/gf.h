@@ -220,10 +220,11 @@ gf_status gf_fuse_pack(const gf_plan *plan, uint32_t phase,
 /* --------------------------------------------------------- gf_fuse_pack_range
  * gf_fuse_pack over the chunks [chunk_lo, chunk_hi) only, for a caller that
  * packs the important chunks while backward is still filling the pool
- * (Section 3.2: "if an important chunk is filled, CSC copies its data to a
- * buffer; when the buffer size is greater than a given threshold, CSC starts
- * an allreduce"; Section 3.1, enable-overlap setting): once the gradients of
- * pool elements [chunk_lo * C, min(N, chunk_hi * C)) exist, this call does for
+ * (Section 3.2: an important chunk is copied into the packed buffer as soon as
+ * backward has filled it, and the buffer is handed to allreduce whenever what
+ * waits in it exceeds the threshold; Section 3.1, enable-overlap setting): once
+ * the gradients of pool elements [chunk_lo * C, min(N, chunk_hi * C)) exist, this
+ * call does for
  * those chunks exactly what gf_fuse_pack does for all of them -- sel_idx / k
  * are still the whole selection, the j-th selected chunk still lands at
  * element j*C of the send buffers, chunk_l1 entries outside the range are not

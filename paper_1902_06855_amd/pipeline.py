@@ -319,9 +319,9 @@ class OverlappedDense:
 
 
 class OverlappedCsc:
-    """Coarse-grained sparse communication with the enable-overlap setting (Section 3.2: "if an
-    important chunk is filled, CSC copies its data to a buffer; when the buffer size is greater
-    than a given threshold, CSC starts an allreduce"; Section 3.1): the pool is swept range by
+    """Coarse-grained sparse communication with the enable-overlap setting (Section 3.2: an important
+    chunk goes into the packed buffer as soon as backward has filled it, and the buffer goes to
+    allreduce whenever what waits in it exceeds the threshold; Section 3.1): the pool is swept range by
     range in generation order, each range as soon as its gradients exist, and every bucket of the
     packed buffer is reduced and unpacked right after the sweep that completed it, while the next
     ranges are still being swept.
