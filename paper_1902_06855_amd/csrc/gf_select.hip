@@ -19,29 +19,18 @@ constexpr int SEL_T = 1024;   // threads of the single selecting workgroup
 // chunk) that are finished here exactly as gf_fuse_pack would have: sub-tiles added in ascending
 // order in fp64, rounded once to fp32.
 // SUBS: -1 finished norms; 1..4 that many partial sums per norm; 0 any number of them (`subs`).
-template <int SUBS>
-__global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1, const double *__restrict__ part,
-                                                    int32_t subs, int32_t P, int32_t nc,
-                                                    const float *__restrict__ red_l1,
-                                                    const int32_t *__restrict__ prev_sel, int32_t k_prev,
-                                                    float *__restrict__ score)
+__device__ __forceinline__ float sent_score(float reduced_norm, int32_t P)
 {
-    const int c = blockIdx.x * GF_BLOCK + threadIdx.x;
-    if (c >= nc) return;
-    if (prev_sel) {
-        int lo = 0, hi = k_prev;                  // first position with prev_sel[pos] >= c (ascending list)
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (prev_sel[mid] < c) lo = mid + 1; else hi = mid;
-        }
-        if (lo < k_prev && prev_sel[lo] == c) {
-            const double share = static_cast<double>(red_l1[lo]) / static_cast<double>(P);
-            double s = 0.0;
-            for (int p = 0; p < P; ++p) s += share;
-            score[c] = static_cast<float>(s);
-            return;
-        }
-    }
+    const double share = static_cast<double>(reduced_norm) / static_cast<double>(P);
+    double s = 0.0;
+    for (int p = 0; p < P; ++p) s += share;
+    return static_cast<float>(s);
+}
+
+template <int SUBS>
+__device__ __forceinline__ float local_score(const float *__restrict__ l1, const double *__restrict__ part,
+                                             int32_t subs, int32_t P, int32_t nc, int c)
+{
     // the norm of worker p, finished
     auto norm = [&](int p) {
         if constexpr (SUBS < 0) {
@@ -71,7 +60,30 @@ __global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1
         for (int u = 0; u < B; ++u) s += static_cast<double>(x[u]);
     }
     for (; p < P; ++p) s += static_cast<double>(norm(p));
-    score[c] = static_cast<float>(s);
+    return static_cast<float>(s);
+}
+
+template <int SUBS>
+__global__ __launch_bounds__(GF_BLOCK) void k_score(const float *__restrict__ l1, const double *__restrict__ part,
+                                                    int32_t subs, int32_t P, int32_t nc,
+                                                    const float *__restrict__ red_l1,
+                                                    const int32_t *__restrict__ prev_sel, int32_t k_prev,
+                                                    float *__restrict__ score)
+{
+    const int c = blockIdx.x * GF_BLOCK + threadIdx.x;
+    if (c >= nc) return;
+    if (prev_sel) {
+        int lo = 0, hi = k_prev;                  // first position with prev_sel[pos] >= c (ascending list)
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (prev_sel[mid] < c) lo = mid + 1; else hi = mid;
+        }
+        if (lo < k_prev && prev_sel[lo] == c) {
+            score[c] = sent_score(red_l1[lo], P);
+            return;
+        }
+    }
+    score[c] = local_score<SUBS>(l1, part, subs, P, nc, c);
 }
 
 // Monotone map from float order to unsigned order.  A score that is not a number (of either
@@ -185,30 +197,71 @@ __global__ __launch_bounds__(SEL_T) void k_select(const float *__restrict__ scor
 // consecutive chunks [t * KPT, t * KPT + KPT), reads their scores once (128-bit loads), runs the
 // four radix passes on registers, and one scan over the threads' counts places its chunks in the
 // ascending output.  For n_chunks <= 1024 * KPT; the time no longer grows with n_chunks.
-template <int KPT>
-__global__ __launch_bounds__(SEL_T) void k_select_reg(const float *__restrict__ score, int32_t nc, int32_t k,
+//
+// SCORE = SCORE_GIVEN: the scores are read from `score`.  Otherwise (few workers, so that one
+// workgroup can read every norm) the kernel computes them first, as k_score<SCORE> would, writes
+// them to `score` and goes on with them in registers: one launch instead of two.  Which chunks
+// were sent is then looked up in an LDS table (chunk -> position in prev_sel) instead of a search.
+constexpr int SCORE_GIVEN = -2;
+
+struct ScoreArgs {
+    const float *l1;
+    const double *part;
+    const float *red_l1;
+    const int32_t *prev_sel;          // may be the output `sel`: read in full before the first barrier
+    int32_t subs, P, k_prev;
+};
+
+template <int KPT, int SCORE>
+__global__ __launch_bounds__(SEL_T) void k_select_reg(float *__restrict__ score, ScoreArgs sa, int32_t nc, int32_t k,
                                                       int32_t C, int64_t N,
-                                                      int32_t *__restrict__ sel, uint8_t *__restrict__ mask,
+                                                      int32_t *sel /* may be prev_sel */, uint8_t *__restrict__ mask,
                                                       int64_t *__restrict__ packed_len, int32_t *__restrict__ slotmap)
 {
     static_assert(KPT % 4 == 0 && KPT <= 32, "counts of a thread travel in 16 bits");
+    static_assert(SCORE == SCORE_GIVEN || KPT <= 16, "positions in prev_sel travel in 16 bits");
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_tot[SEL_T / 64];
     __shared__ uint32_t s_bin, s_remaining;
+    __shared__ int16_t sent_pos[SCORE == SCORE_GIVEN ? 1 : SEL_T * KPT];
     const int tid = threadIdx.x;
     const int base = tid * KPT;
 
     uint32_t key[KPT];
-    const bool vec = gf_aligned(score, 16);
+    if constexpr (SCORE == SCORE_GIVEN) {
+        const bool vec = gf_aligned(score, 16);
 #pragma unroll
-    for (int i = 0; i < KPT; i += 4) {
-        const int c = base + i;
-        if (vec && c + 3 < nc) {
-            const gf_f32x4 v = *reinterpret_cast<const gf_f32x4 *>(score + c);
-            key[i] = ord_key(v.x); key[i + 1] = ord_key(v.y); key[i + 2] = ord_key(v.z); key[i + 3] = ord_key(v.w);
-        } else {
+        for (int i = 0; i < KPT; i += 4) {
+            const int c = base + i;
+            if (vec && c + 3 < nc) {
+                const gf_f32x4 v = *reinterpret_cast<const gf_f32x4 *>(score + c);
+                key[i] = ord_key(v.x); key[i + 1] = ord_key(v.y); key[i + 2] = ord_key(v.z); key[i + 3] = ord_key(v.w);
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) key[i + j] = c + j < nc ? ord_key(score[c + j]) : 0u;
+                for (int j = 0; j < 4; ++j) key[i + j] = c + j < nc ? ord_key(score[c + j]) : 0u;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) sent_pos[base + i] = -1;
+        __syncthreads();
+        if (sa.prev_sel)
+            for (int j = tid; j < sa.k_prev; j += SEL_T) {
+                const int32_t c = sa.prev_sel[j];
+                if (static_cast<uint32_t>(c) < static_cast<uint32_t>(nc)) sent_pos[c] = static_cast<int16_t>(j);
+            }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const int c = base + i;
+            key[i] = 0u;
+            if (c < nc) {
+                const int j = sent_pos[c];
+                const float sc = j >= 0 ? sent_score(sa.red_l1[j], sa.P)
+                                        : local_score<SCORE>(sa.l1, sa.part, sa.subs, sa.P, nc, c);
+                score[c] = sc;
+                key[i] = ord_key(sc);
+            }
         }
     }
 
@@ -300,6 +353,17 @@ extern "C" gf_status gf_chunk_score_select(const gf_plan *pl, const float *chunk
     const int32_t nc = pl->n_chunks;
 
     const int32_t subs = gf_fuse_subs(pl);
+    const ScoreArgs sa{chunk_l1, part, reduced_l1, prev_sel, subs, pl->P, k_prev};
+    // few workers and few chunks: the selecting workgroup computes the scores itself
+    const bool one_launch = nc <= SEL_T * 8 && static_cast<int64_t>(pl->P) * (chunk_l1 ? 1 : subs) <= 8;
+#define GF_SELECT(K, S) hipLaunchKernelGGL((k_select_reg<K, S>), dim3(1), dim3(SEL_T), 0, st, scores, sa, nc, k, \
+                                           pl->chunk, pl->N, sel_idx, mask, packed_len, slotmap)
+    if (one_launch) {
+        if (nc <= SEL_T * 4) { if (chunk_l1) GF_SELECT(4, -1); else GF_SELECT(4, 0); }
+        else                 { if (chunk_l1) GF_SELECT(8, -1); else GF_SELECT(8, 0); }
+        GF_LAUNCH_CHECK();
+        return GF_OK;
+    }
     const dim3 grid((nc + GF_BLOCK - 1) / GF_BLOCK), block(GF_BLOCK);
 #define GF_SCORE(S) hipLaunchKernelGGL(k_score<S>, grid, block, 0, st, chunk_l1, part, subs, pl->P, nc, reduced_l1, \
                                        prev_sel, k_prev, scores)
@@ -311,12 +375,10 @@ extern "C" gf_status gf_chunk_score_select(const gf_plan *pl, const float *chunk
     else GF_SCORE(0);
 #undef GF_SCORE
     GF_LAUNCH_CHECK();
-#define GF_SELECT(K) hipLaunchKernelGGL(k_select_reg<K>, dim3(1), dim3(SEL_T), 0, st, scores, nc, k, pl->chunk, pl->N, \
-                                        sel_idx, mask, packed_len, slotmap)
-    if (nc <= SEL_T * 4) GF_SELECT(4);
-    else if (nc <= SEL_T * 8) GF_SELECT(8);
-    else if (nc <= SEL_T * 16) GF_SELECT(16);
-    else if (nc <= SEL_T * 32) GF_SELECT(32);
+    if (nc <= SEL_T * 4) GF_SELECT(4, SCORE_GIVEN);
+    else if (nc <= SEL_T * 8) GF_SELECT(8, SCORE_GIVEN);
+    else if (nc <= SEL_T * 16) GF_SELECT(16, SCORE_GIVEN);
+    else if (nc <= SEL_T * 32) GF_SELECT(32, SCORE_GIVEN);
     else
         hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_T), 0, st,
                            scores, nc, k, pl->chunk, pl->N, sel_idx, mask, packed_len, slotmap);

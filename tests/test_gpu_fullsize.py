@@ -274,7 +274,7 @@ def test_csc_full_size_sampled(mods, name, groups):
 
 
 @pytest.mark.parametrize("name", ["resnet50_csc", "alexnet_csc", "resnet50_csc_c4096", "resnet50_csc_c2048",
-                                  "alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb"])
+                                  "resnet50_csc_p1", "alexnet_csc_p1", "alexnet_dense", "resnet50_dense_4mb", "resnet50_dense_64mb"])
 def test_full_size_every_element(mods, name):
     """Every measured configuration compared with the checker on every element, not a sample, in
     the benchmark's launch configuration: for the sparse ones the two-pass first iteration and one
