@@ -306,7 +306,10 @@ def test_select_with_scores_that_are_not_numbers(gfm):
         assert np.array_equal(mask.cpu().numpy(), wmask)
 
 
-@pytest.mark.parametrize("P,nc,k", [(6, 500, 50), (64, 20_000, 333)])   # the second takes the multi-kernel route
+# up to eight workers and 8192 chunks the selecting workgroup computes the scores itself (sent chunks
+# found through a table in LDS); beyond either limit a scoring kernel runs first
+@pytest.mark.parametrize("P,nc,k", [(6, 500, 50), (64, 20_000, 333), (1, 3120, 312), (8, 8192, 8192), (2, 4097, 1500),
+                                    (9, 4000, 400), (4, 8193, 2000), (1, 1, 1)])
 def test_select_after_allreduce_scores_sent_chunks_by_their_reduced_norm(gfm, P, nc, k):
     gf, _ = gfm
     rng = np.random.default_rng(8)
