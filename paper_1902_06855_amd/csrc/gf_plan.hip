@@ -72,19 +72,17 @@ static gf_status build_plan(gf_plan *pl, const int64_t *numel, int32_t m, int64_
     }
     pl->N = run;
 
-    // Lazy allreduce: wait while the waited size is not greater than theta.
-    int64_t start = 0, pos = 0, waited = 0;
+    // Lazy allreduce (Section 3.1): a bucket that starts at pool offset `start` closes at the first
+    // tensor end lying more than theta elements past it; what is left after tensor 1 is flushed.
+    int64_t start = 0;
     for (int32_t j = m - 1; j >= 0; --j) {
-        pos += numel[j];
-        waited += numel[j];
-        if (waited > theta) {
+        const int64_t end = pl->off[j] + numel[j];
+        if (end - start > theta || j == 0) {
             pl->bucket_lo.push_back(start);
-            pl->bucket_hi.push_back(pos);
-            start = pos;
-            waited = 0;
+            pl->bucket_hi.push_back(end);
+            start = end;
         }
     }
-    if (waited > 0) { pl->bucket_lo.push_back(start); pl->bucket_hi.push_back(pos); }
 
     // Work tiles: the chunks themselves for a CSC plan.
     pl->tile = chunk > 0 ? chunk : GF_DENSE_TILE;
@@ -95,7 +93,7 @@ static gf_status build_plan(gf_plan *pl, const int64_t *numel, int32_t m, int64_
 
     // Pieces of tensors per tile, pool order.
     pl->piece_start.assign(static_cast<size_t>(pl->n_tiles) + 1, 0);
-    pos = 0;
+    int64_t pos = 0;
     for (int32_t j = m - 1; j >= 0; --j) {
         int64_t left = numel[j], src = 0;
         while (left > 0) {
