@@ -220,7 +220,7 @@ __global__ __launch_bounds__(SEL_T) void k_select_reg(float *__restrict__ score,
 {
     static_assert(KPT % 4 == 0 && KPT <= 32, "counts of a thread travel in 16 bits");
     static_assert(SCORE == SCORE_GIVEN || KPT <= 16, "positions in prev_sel travel in 16 bits");
-    __shared__ uint32_t hist[256];
+    __shared__ uint32_t hist2[2][256];      // the passes alternate between the two
     __shared__ uint32_t wave_tot[SEL_T / 64];
     __shared__ uint32_t s_bin, s_remaining;
     __shared__ int16_t sent_pos[SCORE == SCORE_GIVEN ? 1 : SEL_T * KPT];
@@ -267,12 +267,23 @@ __global__ __launch_bounds__(SEL_T) void k_select_reg(float *__restrict__ score,
 
     // ---- key of the k-th largest score, one byte per pass
     uint32_t prefix = 0, decided = 0, remaining = static_cast<uint32_t>(k);
-    if (tid < 256) hist[tid] = 0;
+    if (tid < 256) hist2[0][tid] = 0;
     __syncthreads();
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int shift = 24, pass = 0; shift >= 0; shift -= 8, ++pass) {
+        uint32_t *hist = hist2[pass & 1];
+        // Neighbouring chunks often share a digit (in the first pass, sign and exponent, nearly
+        // always): a thread adds each run of equal digits among its keys with one update.
+        uint32_t run_digit = 0, run_len = 0;
 #pragma unroll
-        for (int i = 0; i < KPT; ++i)
-            if (base + i < nc && (key[i] & decided) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
+        for (int i = 0; i < KPT; ++i) {
+            if (base + i < nc && (key[i] & decided) == prefix) {
+                const uint32_t d = (key[i] >> shift) & 255u;
+                if (run_len && d != run_digit) { atomicAdd(&hist[run_digit], run_len); run_len = 0; }
+                run_digit = d;
+                ++run_len;
+            }
+        }
+        if (run_len) atomicAdd(&hist[run_digit], run_len);
         __syncthreads();
         if (tid < 64) {
             // The first wavefront finds the bin of the remaining-th largest key on its own: lane l
@@ -290,13 +301,13 @@ __global__ __launch_bounds__(SEL_T) void k_select_reg(float *__restrict__ score,
                 }
                 above += cnt[j];
             }
+        } else if (tid < 64 + 256) {
+            hist2[(pass + 1) & 1][tid - 64] = 0;                     // meanwhile: the next pass's histogram
         }
         __syncthreads();
         prefix |= s_bin << shift;
         decided |= 255u << shift;
         remaining = s_remaining;
-        if (tid < 256) hist[tid] = 0;                                // for the next pass
-        __syncthreads();
     }
     const uint32_t T = prefix;            // every key above T is taken
     const uint32_t r = remaining;         // plus the first r chunks whose key equals T
