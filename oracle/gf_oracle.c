@@ -24,8 +24,10 @@
  * bookkeeping against the conservation property stated with Algorithm 1 on
  * both wire types; the warm-up chunk counts against hand-worked values.  The
  * same pins run once more against a build of this file under AddressSanitizer
- * and UndefinedBehaviorSanitizer.  End-to-end numeric values: PARITY UNPINNED
- * by the paper (it prints no worked example); they rest on the pins above.
+ * and UndefinedBehaviorSanitizer.  Whole iterations (the paper prints no worked
+ * example): against a job simulated worker by worker in plain Python, whose
+ * workers meet only in the two exchanges of Section 3.2 and pass the packed
+ * buffer hop by hop around the ring, on tiny sizes, every buffer bit for bit.
  *
  * The only parallelism is an OpenMP loop over workers (or over disjoint
  * element ranges of the ring), which changes no arithmetic and no order

@@ -1,0 +1,222 @@
+"""A whole job written the way the paper describes it, as a pin of the checker's whole iteration:
+P separate workers, each with its own gradient tensors and historical gradients, that meet only
+in two exchanges per iteration -- the chunk-norm vector and the packed buffer, the latter passed
+hop by hop around a ring (Section 2.4) -- and that each decide the important chunks on their own
+(Section 3.2: every GPU must arrive at the same set).  Pure Python on tiny sizes, one element at
+a time, numpy only for the roundings to fp32 / fp16; nothing here comes from the checker, and
+the checker's iteration driver must reproduce every buffer of every worker bit for bit.
+"""
+import numpy as np
+import pytest
+
+from oracle import pipeline as op
+
+f32 = np.float32
+
+
+def to_wire(x, wire):
+    return np.float16(x) if wire == "f16" else f32(x)
+
+
+def hop_add(a, b, wire):
+    """What a rank does with a received segment element: add its own, round to the wire type."""
+    return to_wire(f32(a) + f32(b), wire)
+
+
+class Worker:
+    def __init__(self, rank, sizes):
+        self.rank = rank
+        self.N = sum(sizes)
+        self.hg = [f32(0.0)] * self.N
+
+    def place(self, tensors, sizes):
+        """Section 3.1: tensor m is produced first and lies first in the pool."""
+        pool = []
+        for j in reversed(range(len(sizes))):
+            pool.extend(f32(v) for v in tensors[j])
+        return pool
+
+    def accumulate(self, pool):
+        self.acc = [f32(g + h) for g, h in zip(pool, self.hg)]          # Algorithm 1: g + hg
+
+    def local_norms(self, C):
+        out = []
+        for lo in range(0, self.N, C):
+            s = 0.0
+            for v in self.acc[lo:lo + C]:
+                s += abs(float(v))
+            out.append(f32(s))
+        return out
+
+    def pack(self, sel, C, S, mu, wire):
+        """Important chunks go to the send buffer in ascending order; Algorithm 1's two rules
+        for the historical gradient."""
+        self.send = []
+        chosen = set(sel)
+        for c in sel:
+            for v in self.acc[c * C:(c + 1) * C]:
+                self.send.append(to_wire(f32(v * f32(S)), wire))
+        for c in range((self.N + C - 1) // C):
+            for i in range(c * C, min(self.N, (c + 1) * C)):
+                self.hg[i] = f32(0.0) if c in chosen else f32(f32(mu) * self.acc[i])
+
+
+def ring_allreduce(workers, lo, hi, wire):
+    """Ranks r = 0..P-1 each hold buf[lo:hi]; P-1 reduce-scatter hops, P-1 all-gather hops.
+    Segments: equal cuts rounded up to 16 bytes, the trailing ones short or empty."""
+    P = len(workers)
+    n = hi - lo
+    per = -(-n // P)
+    gran = 8 if wire == "f16" else 4
+    seg = -(-per // gran) * gran
+    bounds = [(lo + min(n, s * seg), lo + min(n, (s + 1) * seg)) for s in range(P)]
+    for step in range(P - 1):                                   # reduce-scatter
+        msgs = []
+        for w in workers:
+            s = (w.rank - step) % P
+            a, b = bounds[s]
+            msgs.append(((w.rank + 1) % P, s, list(w.buf[a:b])))
+        for dst, s, data in msgs:
+            a, b = bounds[s]
+            for i, v in enumerate(data):
+                workers[dst].buf[a + i] = hop_add(v, workers[dst].buf[a + i], wire)
+    for step in range(P - 1):                                   # all-gather: copies
+        msgs = []
+        for w in workers:
+            s = (w.rank + 1 - step) % P
+            a, b = bounds[s]
+            msgs.append(((w.rank + 1) % P, s, list(w.buf[a:b])))
+        for dst, s, data in msgs:
+            a, b = bounds[s]
+            workers[dst].buf[a:b] = data
+
+
+def top_k(score, k):
+    order = sorted(range(len(score)), key=lambda c: (-float(score[c]), c))   # ties: lower index first
+    return sorted(order[:k])
+
+
+def exchange_sum(contributions):
+    """The small allreduce of the norm vector: rank 0's value first, double precision, stored single."""
+    out = []
+    for c in range(len(contributions[0])):
+        s = 0.0
+        for p in range(len(contributions)):
+            s += float(contributions[p][c])
+        out.append(f32(s))
+    return out
+
+
+def run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T):
+    """grads[t][p][j]: tensor j (ID order) of worker p at iteration t.  Returns per iteration what
+    every worker ended with."""
+    P = len(grads[0])
+    N = sum(sizes)
+    nc = (N + C - 1) // C
+    workers = [Worker(p, sizes) for p in range(P)]
+    sel = None
+    log = []
+    for t in range(T):
+        for w in workers:
+            w.accumulate(w.place(grads[t][w.rank], sizes))
+        norms = [w.local_norms(C) for w in workers]
+        if schedule == "immediate" or sel is None:
+            sel = top_k(exchange_sum(norms), k)
+        for w in workers:
+            w.pack(sel, C, S, mu, wire)
+            w.buf = list(w.send)
+        L = len(workers[0].send)
+        # lazy allreduce on the packed buffer: a bucket goes out once more than theta is waiting
+        start, waited, pos = 0, 0, 0
+        for c in sel:
+            ln = min(N, (c + 1) * C) - c * C
+            pos += ln
+            waited += ln
+            if waited > theta:
+                ring_allreduce(workers, start, pos, wire)
+                start, waited = pos, 0
+        if waited:
+            ring_allreduce(workers, start, pos, wire)
+        assert pos == L
+        for w in workers[1:]:
+            assert [v.tobytes() for v in w.buf] == [v.tobytes() for v in workers[0].buf], "ranks disagree"
+        # unpack on every worker; each one scores the chunks it received by their norm / P
+        alpha = f32(1.0) / f32(S)
+        out = {}
+        shares = []
+        for w in workers:
+            red_norm, mine = {}, {}
+            for j, c in enumerate(sel):
+                s = 0.0
+                for i in range(min(N, (c + 1) * C) - c * C):
+                    v = f32(f32(w.buf[j * C + i]) * alpha)
+                    mine[c * C + i] = v
+                    s += abs(float(v))
+                red_norm[c] = f32(s)
+            out = mine
+            shares.append([float(red_norm[c]) / P if c in red_norm else float(norms[w.rank][c]) for c in range(nc)])
+        entry = dict(sel=list(sel), send=[list(w.send) for w in workers], reduced=list(workers[0].buf), out=out,
+                     hg=[list(w.hg) for w in workers])
+        if schedule == "lagged":
+            score = exchange_sum(shares)
+            entry["score_post"] = score
+            sel = top_k(score, k)
+            entry["sel_next"] = list(sel)
+        log.append(entry)
+    return log
+
+
+def bits(values, dtype):
+    return np.array(values, dtype=dtype).tobytes()
+
+
+@pytest.mark.parametrize("schedule", ["lagged", "immediate"])
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+@pytest.mark.parametrize("P,sizes,C,k,S,mu,theta", [
+    (3, [7, 13, 5], 4, 3, 128.0, 1.0, 1 << 60),      # 7 chunks, the last one a single element
+    (4, [9, 2, 30], 8, 2, 3.0, 0.5, 1 << 60),        # loss scale that is no power of two, momentum factor
+    (2, [5, 5, 5, 6], 3, 5, 1024.0, 1.0, 5),         # several packed buckets, each its own ring
+    (5, [64], 16, 4, 1.0, 1.0, 16),                  # every chunk sent, more ranks than 16-byte groups per bucket
+    (1, [11, 6], 4, 2, 8.0, 1.0, 1 << 60),           # one worker: the ring is the identity
+])
+def test_checker_iteration_equals_the_cluster_simulation(P, sizes, C, k, S, mu, theta, wire, schedule):
+    rng = np.random.default_rng(P * 1000 + len(sizes))
+    T = 4
+    scale = [10.0 ** rng.uniform(-3, 0) for _ in sizes]
+    grads = [[[(rng.standard_normal(n) * scale[j]).astype(np.float32) for j, n in enumerate(sizes)]
+              for _ in range(P)] for _ in range(T)]
+    log = run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T)
+
+    N = sum(sizes)
+    wt = np.float16 if wire == "f16" else np.float32
+    st = op.new_state(P, N)
+    for t in range(T):
+        pools = np.stack([op.fuse(grads[t][p], sizes) for p in range(P)])
+        out = np.full(N, np.float32(-7.0))
+        r = op.csc_iteration(st, pools, C, k, S, mu, schedule, wire, out=out, theta=theta)
+        e = log[t]
+        assert list(r["sel"]) == e["sel"], f"t={t} selection"
+        for p in range(P):
+            assert np.ascontiguousarray(r["send"][p]).tobytes() == bits(e["send"][p], wt), f"t={t} send of worker {p}"
+            assert st.hg[p].tobytes() == bits(e["hg"][p], np.float32), f"t={t} historical gradient of worker {p}"
+        assert np.ascontiguousarray(r["reduced"]).tobytes() == bits(e["reduced"], wt), f"t={t} reduced"
+        want = np.full(N, np.float32(-7.0))
+        for i, v in e["out"].items():
+            want[i] = v
+        assert out.tobytes() == want.tobytes(), f"t={t} output"
+        if schedule == "lagged":
+            assert np.asarray(r["score_post"], dtype=np.float32).tobytes() == bits(e["score_post"], np.float32), f"t={t} scores"
+            assert list(r["sel_next"]) == e["sel_next"], f"t={t} next selection"
+
+
+def test_the_simulation_itself_sums_what_it_should():
+    """Integers small enough that no rounding happens anywhere: after the ring every rank holds
+    the plain sum, whatever the order, so a wrong segment walk or a lost hop shows."""
+    P, n = 4, 37
+    workers = [Worker(p, [n]) for p in range(P)]
+    for w in workers:
+        w.buf = [np.float16((w.rank + 1) * (i % 7)) for i in range(n)]
+    ring_allreduce(workers, 3, n, "f16")
+    for w in workers:
+        assert [float(v) for v in w.buf[3:]] == [float(10 * (i % 7)) for i in range(3, n)]
+        assert [float(v) for v in w.buf[:3]] == [float((w.rank + 1) * i) for i in range(3)]
