@@ -62,8 +62,8 @@ class Worker:
 
 
 def ring_allreduce(workers, lo, hi, wire):
-    """Ranks r = 0..P-1 each hold buf[lo:hi]; P-1 reduce-scatter hops, P-1 all-gather hops.
-    Segments: equal cuts rounded up to 16 bytes, the trailing ones short or empty."""
+    """The ranks in `workers` (ring order) each hold buf[lo:hi]; n-1 reduce-scatter hops, n-1
+    all-gather hops.  Segments: equal cuts rounded up to 16 bytes, the trailing ones short or empty."""
     P = len(workers)
     n = hi - lo
     per = -(-n // P)
@@ -72,23 +72,46 @@ def ring_allreduce(workers, lo, hi, wire):
     bounds = [(lo + min(n, s * seg), lo + min(n, (s + 1) * seg)) for s in range(P)]
     for step in range(P - 1):                                   # reduce-scatter
         msgs = []
-        for w in workers:
-            s = (w.rank - step) % P
+        for r, w in enumerate(workers):
+            s = (r - step) % P
             a, b = bounds[s]
-            msgs.append(((w.rank + 1) % P, s, list(w.buf[a:b])))
+            msgs.append(((r + 1) % P, s, list(w.buf[a:b])))
         for dst, s, data in msgs:
             a, b = bounds[s]
             for i, v in enumerate(data):
                 workers[dst].buf[a + i] = hop_add(v, workers[dst].buf[a + i], wire)
     for step in range(P - 1):                                   # all-gather: copies
         msgs = []
-        for w in workers:
-            s = (w.rank + 1 - step) % P
+        for r, w in enumerate(workers):
+            s = (r + 1 - step) % P
             a, b = bounds[s]
-            msgs.append(((w.rank + 1) % P, s, list(w.buf[a:b])))
+            msgs.append(((r + 1) % P, s, list(w.buf[a:b])))
         for dst, s, data in msgs:
             a, b = bounds[s]
             workers[dst].buf[a:b] = data
+
+
+def allreduce(workers, lo, hi, wire, groups):
+    """Flat ring, or Section 2.4's hierarchical allreduce: groups of consecutive ranks, the lowest
+    rank of each its master; the partial sum travels from the rank after the master along the
+    group to its last rank and from there to the master; the masters run the ring; the masters
+    hand the result to their groups."""
+    P = len(workers)
+    if groups in (0, P):
+        ring_allreduce(workers, lo, hi, wire)
+        return
+    G = P // groups
+    masters = []
+    for g in range(groups):
+        members = workers[g * G:(g + 1) * G]
+        chain = members[1:] + members[:1]
+        for src, dst in zip(chain, chain[1:]):
+            dst.buf[lo:hi] = [hop_add(v, own, wire) for v, own in zip(src.buf[lo:hi], dst.buf[lo:hi])]
+        masters.append(members[0])
+    ring_allreduce(masters, lo, hi, wire)
+    for g in range(groups):
+        for w in workers[g * G + 1:(g + 1) * G]:
+            w.buf[lo:hi] = list(workers[g * G].buf[lo:hi])
 
 
 def top_k(score, k):
@@ -107,7 +130,7 @@ def exchange_sum(contributions):
     return out
 
 
-def run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T):
+def run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T, groups=0):
     """grads[t][p][j]: tensor j (ID order) of worker p at iteration t.  Returns per iteration what
     every worker ended with."""
     P = len(grads[0])
@@ -133,10 +156,10 @@ def run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T):
             pos += ln
             waited += ln
             if waited > theta:
-                ring_allreduce(workers, start, pos, wire)
+                allreduce(workers, start, pos, wire, groups)
                 start, waited = pos, 0
         if waited:
-            ring_allreduce(workers, start, pos, wire)
+            allreduce(workers, start, pos, wire, groups)
         assert pos == L
         for w in workers[1:]:
             assert [v.tobytes() for v in w.buf] == [v.tobytes() for v in workers[0].buf], "ranks disagree"
@@ -207,6 +230,57 @@ def test_checker_iteration_equals_the_cluster_simulation(P, sizes, C, k, S, mu, 
         if schedule == "lagged":
             assert np.asarray(r["score_post"], dtype=np.float32).tobytes() == bits(e["score_post"], np.float32), f"t={t} scores"
             assert list(r["sel_next"]) == e["sel_next"], f"t={t} next selection"
+
+
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+@pytest.mark.parametrize("P,groups", [(4, 2), (6, 3), (6, 2), (4, 1)])
+def test_checker_iteration_with_the_hierarchical_allreduce(P, groups, wire):
+    rng = np.random.default_rng(P * 10 + groups)
+    sizes, C, k, S, T = [21, 9, 14], 6, 3, 64.0, 3
+    grads = [[[rng.standard_normal(n).astype(np.float32) for n in sizes] for _ in range(P)] for _ in range(T)]
+    log = run_cluster(grads, sizes, C, k, S, 1.0, 13, wire, "lagged", T, groups)
+    wt = np.float16 if wire == "f16" else np.float32
+    st = op.new_state(P, sum(sizes))
+    for t in range(T):
+        pools = np.stack([op.fuse(grads[t][p], sizes) for p in range(P)])
+        r = op.csc_iteration(st, pools, C, k, S, 1.0, "lagged", wire, theta=13, groups=groups)
+        assert list(r["sel"]) == log[t]["sel"] and list(r["sel_next"]) == log[t]["sel_next"]
+        assert np.ascontiguousarray(r["reduced"]).tobytes() == bits(log[t]["reduced"], wt), f"t={t} reduced"
+        for p in range(P):
+            assert st.hg[p].tobytes() == bits(log[t]["hg"][p], np.float32)
+
+
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+@pytest.mark.parametrize("theta", [0, 10, 30, 1 << 60])
+def test_checker_dense_iteration_equals_the_cluster_simulation(theta, wire):
+    """Lazy allreduce without sparsification (Section 3.1): tensors arrive in the order m..1, a
+    bucket goes out when more than theta is waiting, every bucket a ring of its own."""
+    rng = np.random.default_rng(theta % 97)
+    P, sizes, S = 3, [12, 3, 20, 7, 9], 256.0
+    N = sum(sizes)
+    grads = [[(rng.standard_normal(n) * 0.1).astype(np.float32) for n in sizes] for _ in range(P)]
+    workers = [Worker(p, sizes) for p in range(P)]
+    for w in workers:
+        w.buf = [to_wire(f32(v * f32(S)), wire) for v in w.place(grads[w.rank], sizes)]
+    sent = [list(w.buf) for w in workers]
+    start, waited, pos = 0, 0, 0
+    for j in reversed(range(len(sizes))):
+        pos += sizes[j]
+        waited += sizes[j]
+        if waited > theta:
+            ring_allreduce(workers, start, pos, wire)
+            start, waited = pos, 0
+    if waited:
+        ring_allreduce(workers, start, pos, wire)
+    alpha = f32(1.0) / f32(S)
+    want_out = [f32(f32(v) * alpha) for v in workers[-1].buf]
+
+    r = op.dense_iteration(np.stack([op.fuse(grads[p], sizes) for p in range(P)]), sizes, theta, S, wire)
+    wt = np.float16 if wire == "f16" else np.float32
+    for p in range(P):
+        assert np.ascontiguousarray(r["send"][p]).tobytes() == bits(sent[p], wt)
+    assert np.ascontiguousarray(r["reduced"]).tobytes() == bits(workers[0].buf, wt)
+    assert r["out"].tobytes() == bits(want_out, np.float32)
 
 
 def test_the_simulation_itself_sums_what_it_should():
