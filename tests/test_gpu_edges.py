@@ -6,7 +6,7 @@ import torch
 from oracle import binding as ob, pipeline as op
 from paper_1902_06855_amd import workloads as wl
 
-from test_gpu_parity import _run_csc, _run_dense, same_bits, gfm  # noqa: F401  (gfm is a fixture)
+from test_gpu_parity import _run_csc, _run_dense, cpu_grads, pools_np, same_bits, gfm  # noqa: F401  (gfm is a fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -25,6 +25,34 @@ def test_one_worker(gfm, schedule):
 def test_a_single_important_chunk_and_a_single_chunk_pool(gfm, schedule):
     _run_csc(gfm, _wl([3000, 5000], 3, 512, 0.0001), schedule, "gather", T=3, k=1)     # k = 1: argmax
     _run_csc(gfm, _wl([300, 500], 3, 4096, 1.0), schedule, "pool", T=2)                # C > N: one short chunk
+
+
+@pytest.mark.parametrize("groups", [0, 64])
+def test_the_largest_worker_count(gfm, groups):
+    # P = 4096, the most a plan takes: every per-worker table, the 4096-term folds of the ring
+    # (flat, and 64 groups of 64) and the column sum over 4096 norm rows, on a small pool
+    gf, pl = gfm
+    w = _wl([40, 24, 130], 4096, 16, 0.3, theta=50)
+    nc = ob.n_chunks(w.N, w.chunk)
+    k = w.k_for(nc)
+    pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=k, mu=w.mu, wire=w.wire, groups=groups)
+    st = op.new_state(w.P, w.N)
+    for t in range(3):
+        pools = pools_np(cpu_grads(w, t), w.sizes)
+        pipe.set_pools([torch.from_numpy(pools[p]).cuda() for p in range(w.P)])
+        pipe.out_pool.fill_(-3.0)
+        pipe.step()
+        torch.cuda.synchronize()
+        out = np.full(w.N, np.float32(-3.0))
+        r = op.csc_iteration(st, pools, w.chunk, k, w.loss_scale, w.mu, "lagged", w.wire, out=out, theta=w.theta,
+                             groups=groups)
+        L = r["send"].shape[1]
+        assert np.array_equal(pipe.sel.cpu().numpy(), r["sel_next"]), f"t={t} selection"
+        same_bits(pipe.reduced[:L].view(torch.int16), r["reduced"].view(np.int16), f"t={t} reduced")
+        same_bits(pipe.out_pool, out, f"t={t} out")
+        for p in (0, 1, 63, 64, 2047, 4095):
+            same_bits(pipe.send[p][:L].view(torch.int16), r["send"][p].view(np.int16), f"t={t} send[{p}]")
+            same_bits(pipe.residual[p], st.hg[p], f"t={t} hg[{p}]")
 
 
 def test_chunks_of_eight_elements(gfm):
