@@ -434,7 +434,8 @@ def main() -> int:
     if not a.pmc_probe and a.others:
         # the same iterations replayed as HIP graphs (no events inside: whole-iteration time only)
         named = [x for x in a.others.split(",") if x and x != a.workload]
-        for nm in [a.workload] + [x for x in named if "dense" in x][:2] + [x for x in named if x.endswith("_p1")]:
+        for nm in ([a.workload] + [x for x in named if "dense" in x][:2]
+                   + [x for x in named if x.endswith("_p1") or x.endswith("_fp16pool")]):
             wo = wl.config(nm)
             so = max(20, wo.iterations)
             r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2, graph=True)
