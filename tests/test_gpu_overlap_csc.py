@@ -256,3 +256,48 @@ def test_full_size_range_by_range_equals_the_single_sweep(gfm, name):
             assert torch.equal(a.send[p][:L].view(torch.int16), b.send[p][:L].view(torch.int16)), f"t={t} send[{p}]"
         del g
     assert not torch.all(one.out_pool == -1.0)
+
+
+def _draw_ranges(seed):
+    """A random range-by-range configuration: tensors, workers, chunk length, threshold (also at
+    chunk borders), wire type, allreduce order, cut points (also empty-looking single-chunk ranges)."""
+    rng = np.random.default_rng(5000 + seed)
+    P = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+    m = int(rng.integers(1, 9))
+    sizes = [int(rng.choice([rng.integers(1, 40), rng.integers(100, 3000), 8192 + rng.integers(-5, 6),
+                             rng.integers(9000, 40000)])) for _ in range(m)]
+    while P * sum(sizes) > 600_000 and max(sizes) > 64:
+        i = int(np.argmax(sizes))
+        sizes[i] = max(64, sizes[i] // 2 + 3)
+    C = int(rng.choice([8, 13, 64, 250, 1000, 4096, 8192, 8200, 20000]))
+    nc = -(-sum(sizes) // C)
+    theta = int(rng.choice([0, C - 1, C, 2 * C, 3 * C + 1, 1 << 40]))
+    n_cuts = int(rng.integers(0, min(nc, 9)))
+    cuts = sorted(set(int(x) for x in rng.integers(1, nc + 1, size=n_cuts)) | {nc})
+    groups = int(rng.choice([0] + [d for d in range(1, P + 1) if P % d == 0]))
+    return dict(P=P, sizes=sizes, C=C, theta=theta, cuts=cuts, groups=groups, wire=str(rng.choice(["f16", "f32"])),
+                density=float(rng.choice([0.1, 0.3, 0.6, 1.0])), mu=float(rng.choice([1.0, 0.5])),
+                mode=str(rng.choice(["gather", "pool"])), scatter=bool(rng.integers(0, 2)),
+                allgather=bool(rng.integers(0, 2)), S=float(rng.choice([1.0, 128.0, 1000.0])))
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_range_configuration(gfm, seed):
+    gf, pl = gfm
+    c = _draw_ranges(seed)
+    w = wl.Workload(f"ranges{seed}", c["sizes"], P=c["P"], chunk=c["C"], density=c["density"], loss_scale=c["S"],
+                    theta=c["theta"], mu=c["mu"], seed=seed, wire=c["wire"])
+    k = w.k_for(ob.n_chunks(w.N, w.chunk))
+    ov = pl.OverlappedCsc(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k, c["cuts"], mu=w.mu, wire=w.wire,
+                          groups=c["groups"], scatter_out=c["scatter"], allgather=c["allgather"])
+    st = op.new_state(w.P, w.N)
+    for t in range(3):
+        g, pools = pools_of(w, t)
+        if c["mode"] == "gather":
+            ov.pipe.set_gradients([[x.cuda() for x in row] for row in g])
+        else:
+            ov.pipe.set_pools([torch.from_numpy(pools[q]).cuda() for q in range(w.P)])
+        ov.pipe.out_pool.fill_(-6.0)
+        ov.step()
+        torch.cuda.synchronize()
+        check_iteration(ov, w, st, pools, k, w.theta, c["groups"], f"seed {seed}: {c} t={t}")
