@@ -119,7 +119,8 @@ def resident_gradient_sets(w, n_sets: int, mode: str, few_dispatches: bool = Fal
 
 
 def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets: int,
-            sgd=None, graph: bool = False, few_dispatches: bool = False, stage_pass: bool = True):
+            sgd=None, graph: bool = False, few_dispatches: bool = False, stage_pass: bool = True,
+            one_call: bool = False):
     import torch
     from paper_1902_06855_amd import gf, pipeline as pl, workloads as wl
 
@@ -164,8 +165,11 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
     else:
         # inside the timed region: one event per iteration boundary, and events around the dominant
         # stage only (every event is a packet between two kernels and costs a few microseconds)
+        # (one_call: no events inside the iteration at all, so that a steady-state sparse iteration
+        # is the library's single gf_csc_iteration call)
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-        pipe.probe, pipe.probe_only = [], dominant
+        if not one_call:
+            pipe.probe, pipe.probe_only = [], dominant
         t0 = time.perf_counter()
         for i in range(steps):
             marks[i].record()
@@ -173,7 +177,7 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
         marks[steps].record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        probe, pipe.probe = pipe.probe, None
+        probe, pipe.probe = pipe.probe or [], None
         iter_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
 
     ms_per_step = (t1 - t0) * 1e3 / steps
@@ -183,7 +187,7 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
 
     # second pass, outside the timed region: every stage bracketed
     stages = {}
-    if stage_pass and not graph:
+    if stage_pass and not graph and not one_call:
         pipe.probe, pipe.probe_only = [], None
         for _ in range(min(steps, 10)):
             pipe.use_tables(*tables[it % n_sets]); pipe.step(); it += 1
@@ -441,6 +445,18 @@ def main() -> int:
             r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10) if wo.chunk else 2, graph=True)
             others[nm + "+graph"] = {kk: r[kk] for kk in ("P", "N", "schedule", "ms_per_step", "gbs", "bytes_per_step")}
             others[nm + "+graph"]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
+    if not a.pmc_probe and a.others:
+        # sparse iterations issued by one host call each (gf_csc_iteration), no events inside
+        named = [x for x in a.others.split(",") if x and x != a.workload]
+        for nm in [a.workload] + [x for x in named if x.endswith("_csc_p1")]:
+            wo = wl.config(nm)
+            if not wo.chunk:
+                continue
+            so = max(20, wo.iterations)
+            r = run_gpu(nm, so, 5, a.input, a.schedule, min(so, 10), one_call=True)
+            others[nm + "+one_call"] = {kk: r[kk] for kk in ("P", "N", "schedule", "ms_per_step", "median_ms", "min_ms",
+                                                             "gbs", "bytes_per_step")}
+            others[nm + "+one_call"]["frac_of_hbm_peak"] = r["gbs"] / HBM_PEAK_GBS
     if a.ladder and not a.pmc_probe:
         for nm in ("alexnet_dense", "resnet50_dense_4mb", "resnet50_pertensor_fp16"):
             others[nm + "+buckets_on_side_streams"] = run_overlap(nm, 10, 5, 4)

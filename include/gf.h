@@ -365,6 +365,41 @@ gf_status gf_unpack_range(const gf_plan *plan, const void *reduced, int64_t L,
                           float alpha, float *out_pool, void *const *out_tensors,
                           float *reduced_l1, void *workspace, gf_stream stream);
 
+/* ------------------------------------------------------------ gf_csc_iteration
+ * One steady-state iteration of coarse-grained sparse communication in the
+ * paper's schedule (Section 3.2: the important chunks of an iteration are chosen
+ * at the end of the one before; Algorithm 1), issued by one host call as
+ *     gf_fuse_pack (accumulate, chunk norms, pack, historical gradient)
+ *  -> gf_ring_reduce_sim -> gf_unpack_apply -> gf_chunk_score_select
+ * back to back on `stream`, with the chunk norms handed from the first call to
+ * the last through the workspace.  Every buffer ends with the bytes the four
+ * calls leave when made one by one.
+ *
+ * sel_idx [max(k, k_next)], device, in/out: in, the k important chunks of this
+ *   iteration (ascending); out, the k_next chunks chosen for the next one.
+ * packed_len, device int64, in/out: in, the number of elements the k chunks hold
+ *   (as gf_chunk_score_select wrote it for them); out, the same for the next
+ *   selection.
+ * reduced_l1 [k] device out (the norms of the reduced chunks, which the selection
+ *   consumes); scores [n_chunks] and mask [n_chunks]: device out, may be NULL.
+ * modifiers: 0, or GF_PHASE_SLOTS when sel_idx / k are what the last
+ *   gf_chunk_score_select or gf_csc_iteration on this workspace produced (the slot
+ *   map is then not rebuilt).  The call always leaves the new selection's slot map
+ *   in the workspace, so iterations chained on one workspace pass GF_PHASE_SLOTS.
+ * Other arguments as in the four calls; workspace is required.  The first
+ * iteration of a job has no selection yet and is made of the single calls
+ * (accumulate, select, pack, ...).  CSC plans only.  Everything is validated
+ * before the first launch. */
+gf_status gf_csc_iteration(const gf_plan *plan, uint32_t modifiers,
+                           const void *const *grads, const float *const *pools,
+                           float *const *residual,
+                           int32_t *sel_idx, int32_t k, int32_t k_next, int64_t *packed_len,
+                           float loss_scale, float mu, void *const *sendbuf,
+                           void *reduced, void *const *allgather_out,
+                           float alpha, float *out_pool, void *const *out_tensors,
+                           float *reduced_l1, float *scores, uint8_t *mask,
+                           void *workspace, gf_stream stream);
+
 /* ------------------------------------------------------- gf_unpack_sgd_update
  * gf_unpack_apply plus the SGD-update step of Algorithm 1 (momentum SGD
  * correction) in the same pass.  With g = fp32(reduced) * alpha, at every

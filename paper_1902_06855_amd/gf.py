@@ -38,7 +38,7 @@ EXPORTS = (
     "gf_plan_layout", "gf_plan_ring_segment", "gf_plan_tiles", "gf_plan_tile_pieces",
     "gf_plan_workspace_bytes", "gf_plan_warmup_k", "gf_fuse_pack", "gf_fuse_pack_range", "gf_fuse_pack_static",
     "gf_chunk_score_select", "gf_ring_reduce_sim", "gf_ring_reduce_range", "gf_unpack_apply", "gf_unpack_range",
-    "gf_unpack_sgd_update",
+    "gf_unpack_sgd_update", "gf_csc_iteration",
 )
 
 _vp, _i32, _i64, _u32, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_float
@@ -77,6 +77,8 @@ _unpack_range = _sig("gf_unpack_range", C.c_int, _vp, _vp, _i64, _vp, _i32, _i32
 _unpack_apply = _sig("gf_unpack_apply", C.c_int, _vp, _vp, _i64, _vp, _i32, _f32, _vp, _vp, _vp, _vp, _vp)
 _unpack_sgd_update = _sig("gf_unpack_sgd_update", C.c_int, _vp, _vp, _i64, _vp, _i32, _f32, _f32, _f32, _vp, _vp, _vp,
                           _vp, _vp, _vp, _vp, _vp)
+_csc_iteration = _sig("gf_csc_iteration", C.c_int, _vp, _u32, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _f32, _f32, _vp,
+                      _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp)
 
 
 class GfError(RuntimeError):
@@ -267,3 +269,15 @@ def gf_unpack_sgd_update(plan: Plan, reduced, L: int, *, sel_idx=None, k: int = 
                               float(momentum), float(learning_rate), _dptr(w_pool), _dptr(hu_pool),
                               _dptr(w_tensors), _dptr(hu_tensors), _dptr(out_pool), _dptr(reduced_l1),
                               _dptr(workspace), _stream(stream)), "gf_unpack_sgd_update")
+
+
+def gf_csc_iteration(plan: Plan, modifiers: int = 0, *, grads=None, pools=None, residual, sel_idx, k: int,
+                     k_next: Optional[int] = None, packed_len, loss_scale: float = 1.0, mu: float = 1.0, sendbuf,
+                     reduced, allgather_out=None, alpha: float = 1.0, out_pool=None, out_tensors=None, reduced_l1,
+                     scores=None, mask=None, workspace, stream=None) -> None:
+    """One steady-state lagged iteration (fuse-pack, allreduce, unpack, select) in one call."""
+    _check(_csc_iteration(plan.handle, int(modifiers), _dptr(grads), _dptr(pools), _dptr(residual), _dptr(sel_idx),
+                          int(k), int(k if k_next is None else k_next), _dptr(packed_len), float(loss_scale),
+                          float(mu), _dptr(sendbuf), _dptr(reduced), _dptr(allgather_out), float(alpha),
+                          _dptr(out_pool), _dptr(out_tensors), _dptr(reduced_l1), _dptr(scores), _dptr(mask),
+                          _dptr(workspace), _stream(stream)), "gf_csc_iteration")

@@ -225,10 +225,22 @@ class Pipeline:
             self._run("pack", self.pack); self._run("ring", self.ring); self._run("unpack", self.unpack)
             if self.schedule == "lagged":
                 self._run("select", self.select, True)
+        elif self.fast and self.sgd is None and self.probe is None:
+            self.iteration()
         else:
             self._run("fused", self.fused); self._run("ring", self.ring); self._run("unpack", self.unpack)
             self._run("select", self.select, True)
         self.t += 1
+
+    def iteration(self) -> None:
+        """A steady-state lagged iteration as one call into the library (the same four launches)."""
+        gf.gf_csc_iteration(self.plan, gf.GF_PHASE_SLOTS, grads=self.grads_tab, pools=self.pools_tab,
+                            residual=self.residual_tab, sel_idx=self.sel, k=self.k, k_next=self.k_next,
+                            packed_len=self.packed_len, loss_scale=self.S, mu=self.mu, sendbuf=self.send_tab,
+                            reduced=self.reduced, allgather_out=self.ag_tab, alpha=self.alpha,
+                            out_pool=self.out_pool, out_tensors=self.out_tab, reduced_l1=self.red_l1,
+                            scores=self.scores, mask=self.mask, workspace=self.ws)
+        self.k = self.k_next
 
 
 class OverlappedDense:

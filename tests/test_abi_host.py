@@ -291,3 +291,35 @@ def test_modifier_bits_and_range_calls_validate_before_touching_the_gpu():
     big = gf.Plan([5000 * 8200], 1 << 40, 8200, 64, to_device=False)
     assert big.workspace_bytes() > gf.GF_STATIC_SCRATCH_BYTES
     assert status(gf.gf_fuse_pack_static, big, A, pools=fake, residual=fake, chunk_l1=fake) == Lim
+
+
+def test_the_one_call_iteration_validates_everything_before_the_first_launch():
+    csc = gf.Plan([4096, 4096], 1 << 40, 1024, 2, to_device=False)        # 8 chunks
+    dense = gf.Plan([4096, 4096], 1 << 40, 0, 2, to_device=False)
+    fake, ws = 0x1000, 0x100
+    E, S = gf.GF_EINVAL, gf.GF_ESTATE
+
+    def status(plan, modifiers=0, **change):
+        kw = dict(pools=fake, residual=fake, sel_idx=fake, k=2, k_next=3, packed_len=fake, sendbuf=fake,
+                  reduced=fake, out_pool=fake, reduced_l1=fake, workspace=ws)
+        kw.update(change)
+        with pytest.raises(gf.GfError) as e:
+            gf.gf_csc_iteration(plan, modifiers, stream=0, **kw)
+        return e.value.status
+
+    assert status(csc) == S                                               # valid, but not uploaded
+    assert status(csc, gf.GF_PHASE_SLOTS, scores=fake, mask=fake, allgather_out=fake) == S
+    assert status(dense) == E                                             # needs chunks
+    assert status(csc, gf.GF_PHASE_DEFER_NORMS) == E                      # the only modifier is the slot map's
+    assert status(csc, 16) == E
+    assert status(csc, grads=fake) == E                                   # both gradient forms
+    assert status(csc, pools=None) == E                                   # neither
+    for missing in ("residual", "sel_idx", "packed_len", "sendbuf", "reduced", "reduced_l1", "workspace"):
+        assert status(csc, **{missing: None}) == E, missing
+    assert status(csc, out_pool=None) == E                                # nowhere to write
+    assert status(csc, out_pool=None, out_tensors=fake) == S
+    assert status(csc, k=0) == E
+    assert status(csc, k=9) == E
+    assert status(csc, k_next=0) == E
+    assert status(csc, k_next=9) == E
+    assert status(csc, workspace=0x104) == E

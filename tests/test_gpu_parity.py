@@ -911,3 +911,63 @@ def test_bucket_wise_iteration_replayed_as_a_graph(gfm):
         torch.randn(1 << 14, device="cuda").sum().item()                     # unrelated eager work in between
         same_bits(ov.reduced.view(torch.int16), ref[t]["reduced"].view(np.int16), f"replay {it} reduced")
         same_bits(ov.out_pool, ref[t]["out"], f"replay {it} out")
+
+
+# ------------------------------------------- one host call per steady-state iteration
+
+@pytest.mark.parametrize("wire", ["f16", "f32"])
+@pytest.mark.parametrize("mode", ["gather", "pool"])
+def test_one_call_iteration_equals_the_four_calls(gfm, mode, wire):
+    """gf_csc_iteration against the same iteration made of the four calls (two pipelines fed the
+    same gradients), over iterations whose chunk count changes, with all-gather copies and
+    per-tensor outputs, the slot map rebuilt (modifiers 0) or handed over; and against the checker."""
+    gf, pl = gfm
+    w = odd_workload(P=3, chunk=250, wire=wire, density=0.3)
+    nc = ob.n_chunks(w.N, w.chunk)
+    ks = [w.k_for(nc), w.k_for(nc), max(1, nc // 2), 2, nc, 3, 3]     # the first iteration keeps its count
+    raw = lambda x: x.contiguous().view(torch.uint8)
+    mk = lambda fast: pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=ks[0], k_max=nc, mu=0.75, wire=wire,
+                                  scatter_out=True, allgather=True, fast=fast)
+    one, four = mk(True), mk(False)                       # `four` never takes the one-call route
+    st = op.new_state(w.P, w.N)
+    for t in range(len(ks) - 1):
+        grads = cpu_grads(w, t)
+        pools = pools_np(grads, w.sizes)
+        for pipe in (one, four):
+            if mode == "gather":
+                pipe.set_gradients(to_dev(grads))
+            else:
+                pipe.set_pools([torch.from_numpy(pools[p]).cuda() for p in range(w.P)])
+            pipe.k_next = ks[t + 1]
+            pipe.out_pool.fill_(-2.0)
+        four.step()
+        if t == 0:
+            one.step()                                    # the first iteration is made of the single calls
+        elif t % 2:
+            one.step()                                    # gf_csc_iteration with the slot map handed over
+        else:
+            gf.gf_csc_iteration(one.plan, 0, grads=one.grads_tab, pools=one.pools_tab, residual=one.residual_tab,
+                                sel_idx=one.sel, k=one.k, k_next=one.k_next, packed_len=one.packed_len,
+                                loss_scale=one.S, mu=one.mu, sendbuf=one.send_tab, reduced=one.reduced,
+                                allgather_out=one.ag_tab, alpha=one.alpha, out_pool=one.out_pool,
+                                out_tensors=one.out_tab, reduced_l1=one.red_l1, workspace=one.ws)   # no scores, no mask
+            one.k = one.k_next
+            one.t += 1
+        torch.cuda.synchronize()
+        out = np.full(w.N, np.float32(-2.0))
+        r = op.csc_iteration(st, pools, w.chunk, ks[t], w.loss_scale, 0.75, "lagged", wire, out=out, k_next=ks[t + 1],
+                             theta=w.theta)
+        L = r["send"].shape[1]
+        what = f"{mode} {wire} t={t}"
+        assert np.array_equal(one.sel.cpu().numpy()[:ks[t + 1]], r["sel_next"]), what
+        assert torch.equal(one.sel[:ks[t + 1]], four.sel[:ks[t + 1]]) and torch.equal(one.packed_len, four.packed_len), what
+        same_bits(one.out_pool, out, what + " out")
+        for a, b in ((one.reduced[:L], four.reduced[:L]), (one.red_l1[:ks[t]], four.red_l1[:ks[t]]),
+                     (one.out_pool, four.out_pool), (one.scores, four.scores) if t % 2 or t == 0 else (one.mask[:0], four.mask[:0])):
+            assert torch.equal(raw(a), raw(b)), what
+        for p in range(w.P):
+            assert torch.equal(raw(one.residual[p]), raw(four.residual[p])), what
+            assert torch.equal(raw(one.send[p][:L]), raw(four.send[p][:L])), what
+            assert torch.equal(raw(one.ag[p][:L]), raw(four.ag[p][:L])), what
+        for a, b in zip(one.out_tensors, four.out_tensors):
+            assert torch.equal(raw(a), raw(b)), what
