@@ -971,3 +971,51 @@ def test_one_call_iteration_equals_the_four_calls(gfm, mode, wire):
             assert torch.equal(raw(one.ag[p][:L]), raw(four.ag[p][:L])), what
         for a, b in zip(one.out_tensors, four.out_tensors):
             assert torch.equal(raw(a), raw(b)), what
+
+
+def test_the_call_sequence_of_a_training_loop(gfm):
+    """The sequence a training loop makes (first iteration from the single calls, every later one
+    with gf_csc_iteration), through the binding alone, against the checker."""
+    gf, _ = gfm
+    w = odd_workload(P=2, chunk=512, density=0.25)
+    P, N, C, S = w.P, w.N, w.chunk, w.loss_scale
+    plan = gf.Plan(w.sizes, w.theta, C, P)
+    nc = plan.n_chunks
+    k = w.k_for(nc)
+    ws = plan.workspace()
+    dev = lambda n, dt: torch.zeros(n, dtype=dt, device="cuda")
+    hg = [dev(N, torch.float32) for _ in range(P)]
+    send = [dev(k * C, torch.float16) for _ in range(P)]
+    hg_tab, send_tab = gf.ptr_table(hg), gf.ptr_table(send)
+    sel, L_dev, rl1 = dev(k, torch.int32), dev(1, torch.int64), dev(k, torch.float32)
+    reduced, out = dev(k * C, torch.float16), dev(N, torch.float32)
+    alpha = float(np.float32(1.0) / np.float32(S))
+    st = op.new_state(P, N)
+    for t in range(4):
+        grads = cpu_grads(w, t)
+        g_dev = to_dev(grads)
+        grads_tab = gf.ptr_table([x for row in g_dev for x in row])
+        out.fill_(-1.0)
+        if t == 0:
+            gf.gf_fuse_pack(plan, gf.GF_PHASE_ACCUM | gf.GF_PHASE_DEFER_NORMS, grads=grads_tab, residual=hg_tab,
+                            workspace=ws)
+            gf.gf_chunk_score_select(plan, None, k=k, sel_idx=sel, packed_len=L_dev, workspace=ws)
+            gf.gf_fuse_pack(plan, gf.GF_PHASE_PACK | gf.GF_PHASE_SLOTS, residual=hg_tab, sel_idx=sel, k=k,
+                            loss_scale=S, sendbuf=send_tab, workspace=ws)
+            gf.gf_ring_reduce_sim(plan, send_tab, k * C, reduced, L_dev=L_dev)
+            gf.gf_unpack_apply(plan, reduced, k * C, sel_idx=sel, k=k, alpha=alpha, out_pool=out, reduced_l1=rl1)
+            gf.gf_chunk_score_select(plan, None, reduced_l1=rl1, prev_sel=sel, k_prev=k, k=k, sel_idx=sel,
+                                     packed_len=L_dev, workspace=ws)
+        else:
+            gf.gf_csc_iteration(plan, gf.GF_PHASE_SLOTS, grads=grads_tab, residual=hg_tab, sel_idx=sel, k=k,
+                                packed_len=L_dev, loss_scale=S, sendbuf=send_tab, reduced=reduced, alpha=alpha,
+                                out_pool=out, reduced_l1=rl1, workspace=ws)
+        torch.cuda.synchronize()
+        want = np.full(N, np.float32(-1.0))
+        r = op.csc_iteration(st, pools_np(grads, w.sizes), C, k, S, w.mu, "lagged", out=want, theta=w.theta)
+        L = r["send"].shape[1]
+        assert np.array_equal(sel.cpu().numpy(), r["sel_next"]), f"t={t}"
+        same_bits(out, want, f"t={t} out")
+        same_bits(reduced[:L].view(torch.int16), r["reduced"].view(np.int16), f"t={t} reduced")
+        for p in range(P):
+            same_bits(hg[p], st.hg[p], f"t={t} hg[{p}]")
