@@ -325,3 +325,27 @@ def test_the_one_call_iteration_validates_everything_before_the_first_launch():
     assert status(csc, k_next=0) == E
     assert status(csc, k_next=9) == E
     assert status(csc, workspace=0x104) == E
+
+
+def test_the_header_is_plain_c(tmp_path):
+    """include/gf.h is the boundary for C callers: it must compile as C99 on its own, and a C
+    program must link against the library and reach a host-only call."""
+    import subprocess
+    src = tmp_path / "use_gf.c"
+    src.write_text(
+        '#include "gf.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "    int64_t numel[3] = {5, 7, 11}, N = 0; int32_t nc = 0, nb = 0; gf_plan *p = 0;\n"
+        "    if (gf_plan_create(&p, numel, 3, 6, 4, 2, GF_WIRE_F16) != GF_OK) return 1;\n"
+        "    if (gf_plan_info(p, &N, &nc, &nb) != GF_OK) return 2;\n"
+        '    printf("%lld %d %d %s\\n", (long long)N, nc, nb, gf_status_string(GF_ELIMIT));\n'
+        "    gf_plan_destroy(p);\n    return 0;\n}\n")
+    exe = tmp_path / "use_gf"
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.dirname(gf_build.LIB)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                    os.path.join(inc, "gf.h")], check=True)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe), "-L", libdir,
+                    "-l:libgf.so", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out[:3] == ["23", "6", "3"]          # 23 elements, 6 chunks of 4, buckets {11}, {7} (7 > 6), {5}
