@@ -58,7 +58,7 @@ _ring_fold = _sig("gfo_ring_fold", None, C.c_int, _vp, _i64, _i32, _vp)
 _hier_hops = _sig("gfo_hier_allreduce_hops", None, C.c_int, _vp, _i64, _i32, _i32, _vp)
 _hier_fold = _sig("gfo_hier_fold", None, C.c_int, _vp, _i64, _i32, _i32, _vp)
 _unpack = _sig("gfo_unpack", None, C.c_int, _vp, _i64, _i64, _vp, _i32, _f32, _vp, _vp)
-_sgd_update = _sig("gfo_sgd_update", None, C.c_int, _vp, _i64, _i64, _vp, _i32, _f32, _f32, _f32, _vp, _vp, _vp)
+_sgd_update = _sig("gfo_sgd_update", None, C.c_int, _vp, _i64, _i64, _vp, _i32, _f32, _f32, _f32, _vp, _vp, _vp, _vp)
 _unpack_dense = _sig("gfo_unpack_dense", None, C.c_int, _vp, _i64, _f32, _vp)
 
 WIRE = {"f16": 0, "f32": 1}
@@ -263,14 +263,16 @@ def unpack(reduced: np.ndarray, N: int, Cc: int, sel: np.ndarray, alpha: float,
 
 def sgd_update(reduced: np.ndarray, N: int, Cc: int, sel: np.ndarray, alpha: float, momentum: float,
                lr: float, w: np.ndarray, hu: np.ndarray, out: Optional[np.ndarray] = None,
-               wire: str = "f16") -> None:
-    """Algorithm 1's update step on the important chunks; w, hu (and out) [N] are updated in place."""
+               wire: str = "f16", w_half: Optional[np.ndarray] = None) -> None:
+    """Algorithm 1's update step on the important chunks; w, hu (and out, and the FP16 copy of the
+    weights w_half, uint16 bit patterns) [N] are updated in place."""
     assert reduced.dtype == WIRE_DTYPE[wire] and w.dtype == np.float32 and hu.dtype == np.float32
     assert w.size == N and hu.size == N and (out is None or (out.dtype == np.float32 and out.size == N))
+    assert w_half is None or (w_half.dtype == np.uint16 and w_half.size == N)
     sel = np.ascontiguousarray(sel, dtype=np.int32)
     assert reduced.size == packed_len(N, Cc, sel)
     _sgd_update(WIRE[wire], _ptr(reduced), int(N), int(Cc), _ptr(sel), len(sel), float(alpha),
-                float(momentum), float(lr), _ptr(w), _ptr(hu), _ptr(out))
+                float(momentum), float(lr), _ptr(w), _ptr(hu), _ptr(out), _ptr(w_half))
 
 
 def unpack_dense(reduced: np.ndarray, alpha: float, wire: str = "f16") -> np.ndarray:

@@ -593,10 +593,13 @@ void gfo_unpack(int wire, const void *reduced, int64_t N, int64_t C,
 /* ------------------------------ Algorithm 1, SGD update step (Sec. 3.2)
  * For a gradient in an important chunk: u = hu = momentum * hu + learningrate * g
  * and w = w + u.  Anywhere else hu keeps its value and w is not updated.
- * g is the unpacked reduced gradient; out (optional) receives it. */
+ * g is the unpacked reduced gradient; out (optional) receives it.
+ * Mixed precision (Sec. 2.5): the update works on FP32 values, forward and
+ * backward on FP16 parameters; w_half (optional) is that FP16 copy, rewritten
+ * from the new FP32 weight wherever a weight changed (one conversion each). */
 void gfo_sgd_update(int wire, const void *reduced, int64_t N, int64_t C,
                     const int32_t *sel, int32_t k, float alpha, float momentum, float lr,
-                    float *w, float *hu, float *out)
+                    float *w, float *hu, float *out, uint16_t *w_half)
 {
     int64_t slot = 0;
     for (int32_t j = 0; j < k; ++j) {
@@ -611,6 +614,7 @@ void gfo_sgd_update(int wire, const void *reduced, int64_t N, int64_t C,
             float u = keep + step;
             hu[lo + i] = u;
             w[lo + i] = w[lo + i] + u;
+            if (w_half) w_half[lo + i] = gfo_f32_to_f16(w[lo + i]);
         }
         slot += len;
     }

@@ -79,3 +79,42 @@ def test_momentum_zero_unit_rate_accumulates_the_gradient():
     assert np.array_equal(w[64:128], np.arange(64, dtype=np.float32))
     assert np.array_equal(w[192:256], np.arange(64, 128, dtype=np.float32))
     assert np.all(w[:64] == 0) and np.all(hu[:64] == 7.0)
+
+
+def test_half_precision_copy_of_the_weights_follows_the_updated_ones():
+    """Section 2.5: the update runs on FP32 values, forward and backward use FP16 parameters.  The
+    FP16 copy is the new FP32 weight rounded once (numpy's float16 does the rounding here), only
+    where a weight changed; everywhere else it keeps its bits.  One conversion per updated
+    parameter: with every chunk important that is N of them, the paper's count for AlexNet."""
+    rng = np.random.default_rng(5)
+    N, C = 1000, 96
+    nc = ob.n_chunks(N, C)
+    for wire in ("f16", "f32"):
+        sel = np.array(sorted(rng.choice(nc, size=4, replace=False)), dtype=np.int32)
+        if nc - 1 not in sel:
+            sel[-1] = nc - 1                                   # the short last chunk is among them
+        L = ob.packed_len(N, C, sel)
+        g = (rng.standard_normal(L) * 1e-5).astype(np.float32)  # small steps: the weights keep their binades
+        red = ob.f32_to_f16(g) if wire == "f16" else g
+        # weights over many binades, some beyond what FP16 holds, some below its smallest normal
+        w = (rng.standard_normal(N) * 10.0 ** rng.integers(-9, 7, size=N)).astype(np.float32)
+        hu = (rng.standard_normal(N) * 1e-7).astype(np.float32)
+        w_half = np.full(N, 0x1234, dtype=np.uint16)
+        w0 = w.copy()
+        ob.sgd_update(red, N, C, sel, np.float32(0.5), 0.9, -0.25, w, hu, None, wire, w_half=w_half)
+        touched = np.zeros(N, dtype=bool)
+        for c in sel:
+            touched[c * C:(c + 1) * C] = True
+        assert np.array_equal(w[~touched], w0[~touched]) and not np.array_equal(w[touched], w0[touched])
+        with np.errstate(over="ignore"):
+            want = w.astype(np.float16).view(np.uint16)
+        assert np.array_equal(w_half[touched], want[touched])
+        assert np.all(w_half[~touched] == 0x1234)
+        assert np.isinf(want[touched].view(np.float16)).any() and (np.abs(w[touched]) < 6e-5).any()
+    # every chunk important: exactly N conversions
+    sel = np.arange(nc, dtype=np.int32)
+    w_half = np.zeros(N, dtype=np.uint16)
+    w = rng.standard_normal(N).astype(np.float32)
+    ob.sgd_update(ob.f32_to_f16(np.ones(N, dtype=np.float32)), N, C, sel, np.float32(1), 0.0, 1.0, w,
+                  np.zeros(N, dtype=np.float32), None, "f16", w_half=w_half)
+    assert np.array_equal(w_half, w.astype(np.float16).view(np.uint16))
