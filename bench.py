@@ -65,8 +65,8 @@ def algorithmic_bytes(w, k_elems_L: int, schedule: str, sgd: bool = False):
     else:
         st = {"accum": P * N * (gs + 8), "pack": P * L * (4 + ws + 4), "ring": L * (P * ws + ws),
               "unpack": L * (ws + 4), "select": 0}
-    if sgd:                                   # Algorithm 1's update step: hu and w read and written
-        st["unpack"] += L * 16
+    if sgd:                                   # Algorithm 1's update step: hu and w read and written,
+        st["unpack"] += L * 18                #   the FP16 copy of the updated weights written (Section 2.5)
     return sum(st.values()), st
 
 
@@ -132,7 +132,8 @@ def run_gpu(name: str, steps: int, warmup: int, mode: str, schedule: str, n_sets
         pipe_k = w.k_for(probe_plan.n_chunks)
         probe_plan.close()
     pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=pipe_k, mu=w.mu, wire=w.wire,
-                       schedule=schedule, sgd=sgd, grad=w.grad, zero_copy=bool(w.extra.get("zero_copy")),
+                       schedule=schedule, sgd=sgd, half_weights=sgd is not None, grad=w.grad,
+                       zero_copy=bool(w.extra.get("zero_copy")),
                        groups=int(w.extra.get("groups", 0)))
     if w.extra.get("zero_copy"):
         mode = "pool"
@@ -463,7 +464,7 @@ def main() -> int:
         for nm in ("alexnet_csc", "resnet50_csc"):
             others[nm + "+ranges_and_buckets_as_they_fill"] = run_overlap_csc(nm, 10, 5)
     if w.chunk and not a.pmc_probe and a.others:
-        # the same workload with Algorithm 1's SGD-update step fused into the unpack
+        # the same workload with Algorithm 1's SGD-update step (and the FP16 weight copy) fused into the unpack
         r = run_gpu(a.workload, steps, warmup, a.input, a.schedule, n_sets, sgd=(0.9, -0.01))
         others[a.workload + "+sgd_update"] = {kk: r[kk] for kk in ("P", "N", "schedule", "ms_per_step", "gbs",
                                                                       "bytes_per_step", "stages")}

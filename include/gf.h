@@ -411,14 +411,22 @@ gf_status gf_csc_iteration(const gf_plan *plan, uint32_t modifiers,
  * the caller passes a negative learning_rate for descent.
  * w / hu come either as N-element fp32 pools in the plan's layout (w_pool,
  * hu_pool) or as device tables [m] of per-tensor fp32 buffers (w_tensors,
- * hu_tensors); exactly one of the two forms.  out_pool (optional) also
- * receives g as gf_unpack_apply would write it.  Other arguments as in
- * gf_unpack_apply. */
+ * hu_tensors); exactly one of the two forms.
+ * w_half_pool / w_half_tensors: NULL, or the FP16 copy of the weights that
+ *   forward and backward use under mixed precision (Section 2.5: FP16
+ *   parameters there, FP32 values in the update), in the same form as w (an
+ *   N-element binary16 pool, or a device table [m] of per-tensor binary16
+ *   buffers; GF_EINVAL if the form differs).  Wherever a weight is updated its
+ *   FP16 copy is rewritten from the new fp32 value (one conversion); the other
+ *   elements are not touched.
+ * out_pool (optional) also receives g as gf_unpack_apply would write it.  Other
+ * arguments as in gf_unpack_apply. */
 gf_status gf_unpack_sgd_update(const gf_plan *plan, const void *reduced, int64_t L,
                                const int32_t *sel_idx, int32_t k, float alpha,
                                float momentum, float learning_rate,
                                float *w_pool, float *hu_pool,
                                void *const *w_tensors, void *const *hu_tensors,
+                               void *w_half_pool, void *const *w_half_tensors,
                                float *out_pool, float *reduced_l1,
                                void *workspace, gf_stream stream);
 

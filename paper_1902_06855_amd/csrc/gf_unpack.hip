@@ -17,6 +17,8 @@ struct UnpackArgs {
     void *const *out_tensors;
     float *w_pool, *hu_pool;       // update variant, pool form
     void *const *w_tensors, *const *hu_tensors;   // update variant, per-tensor form
+    uint16_t *wh_pool;             // update variant: FP16 copy of the weights (optional), pool form
+    void *const *wh_tensors;       //                 the same, per-tensor form
     float *reduced_l1;
     const int32_t *piece_start;
     const gf_piece *pieces;
@@ -31,19 +33,21 @@ struct UnpackArgs {
 // log2 of the consecutive tiles one XCD takes
 constexpr int UNPACK_GRP_SHIFT = 4;
 
-// One contiguous run.  dst may be null in the update variant (gradient not kept).
+// One contiguous run.  dst may be null in the update variant (gradient not kept); wh (the FP16
+// copy of the weights, Section 2.5) may be null.
 template <typename W, bool UPD, int NT>
-__device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, float *w_, int len,
+__device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, float *w_, uint16_t *wh_, int len,
                                     const UnpackArgs &a, double &l1)
 {
     const GF_GLOBAL W *__restrict__ src = gf_global(src_);
     GF_GLOBAL float *__restrict__ dst = gf_global(dst_);
     GF_GLOBAL float *__restrict__ hu = gf_global(hu_);
     GF_GLOBAL float *__restrict__ w = gf_global(w_);
+    GF_GLOBAL uint16_t *__restrict__ wh = gf_global(wh_);
     using W4 = typename gf_wire4<W>::type;
     const float alpha = a.alpha, mom = a.momentum, lr = a.lr;
     bool vec = gf_aligned(src, sizeof(W4)) && (!dst || gf_aligned(dst, 16));
-    if constexpr (UPD) vec = vec && gf_aligned(hu, 16) && gf_aligned(w, 16);
+    if constexpr (UPD) vec = vec && gf_aligned(hu, 16) && gf_aligned(w, 16) && (!wh || gf_aligned(wh, 8));
     const int nvec = vec ? (len >> 2) : 0;
     // Streams go through buffer descriptors made for exactly this run: the reduced values were
     // just written by the ring kernel (cached loads); everything written here is not read again
@@ -54,6 +58,7 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
     const __amdgpu_buffer_rsrc_t db = gf_make_buf(dst, dst ? n4 : 0u);
     const __amdgpu_buffer_rsrc_t hb = gf_make_buf(hu, UPD ? n4 : 0u);
     const __amdgpu_buffer_rsrc_t wb = gf_make_buf(w, UPD ? n4 : 0u);
+    const __amdgpu_buffer_rsrc_t whb = gf_make_buf(wh, (UPD && wh) ? n4 / 2u : 0u);
     auto ld_src = [&](int v) {
         if constexpr (sizeof(W) == 2) return gf_buf_ld64u<GF_AUX_CACHED>(sb, v * WB);
         else return gf_buf_ld128<GF_AUX_CACHED>(sb, v * WB);
@@ -71,7 +76,10 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
             const gf_f32x4 hn = gf_pack4(mom * hh.x + lr * g0, mom * hh.y + lr * g1,
                                          mom * hh.z + lr * g2, mom * hh.w + lr * g3);
             gf_buf_st<GF_AUX_STREAM>(hn, hb, v * 16);
-            gf_buf_st<GF_AUX_STREAM>(gf_pack4(ww.x + hn.x, ww.y + hn.y, ww.z + hn.z, ww.w + hn.w), wb, v * 16);
+            const gf_f32x4 wn = gf_pack4(ww.x + hn.x, ww.y + hn.y, ww.z + hn.z, ww.w + hn.w);
+            gf_buf_st<GF_AUX_STREAM>(wn, wb, v * 16);
+            if (wh) gf_buf_st<GF_AUX_STREAM>(gf_pack4(gf_f32_to_h(wn.x), gf_f32_to_h(wn.y), gf_f32_to_h(wn.z),
+                                                      gf_f32_to_h(wn.w)), whb, v * 8);
         }
     };
 
@@ -116,7 +124,9 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
         if constexpr (UPD) {
             const float hn = mom * hu[i] + lr * g;
             hu[i] = hn;
-            w[i] = w[i] + hn;
+            const float wn = w[i] + hn;
+            w[i] = wn;
+            if (wh) wh[i] = gf_f32_to_h(wn);
         }
     }
 }
@@ -139,8 +149,10 @@ __global__ __launch_bounds__(NT) void k_unpack(const UnpackArgs a)
     const bool pooled = a.out_pool || (UPD && a.w_pool);
     if (pooled) {
         float *out = a.out_pool ? a.out_pool + tile_lo : nullptr;
-        if (UPD && a.w_pool) run<W, UPD, NT>(src, out, a.hu_pool + tile_lo, a.w_pool + tile_lo, tile_len, a, l1);
-        else run<W, false, NT>(src, out, nullptr, nullptr, tile_len, a, l1);
+        if (UPD && a.w_pool)
+            run<W, UPD, NT>(src, out, a.hu_pool + tile_lo, a.w_pool + tile_lo,
+                            a.wh_pool ? a.wh_pool + tile_lo : nullptr, tile_len, a, l1);
+        else run<W, false, NT>(src, out, nullptr, nullptr, nullptr, tile_len, a, l1);
     }
     if (a.out_tensors || (UPD && a.w_tensors)) {
         // per-tensor destinations: walk the pieces of this tile
@@ -151,12 +163,13 @@ __global__ __launch_bounds__(NT) void k_unpack(const UnpackArgs a)
             float *dst = a.out_tensors ? static_cast<float *>(a.out_tensors[pc.tensor]) + pc.src_off : nullptr;
             if constexpr (UPD) {
                 if (a.w_tensors) {
+                    uint16_t *wh = a.wh_tensors ? static_cast<uint16_t *>(a.wh_tensors[pc.tensor]) + pc.src_off : nullptr;
                     run<W, true, NT>(src + pc.dst_rel, dst, static_cast<float *>(a.hu_tensors[pc.tensor]) + pc.src_off,
-                                 static_cast<float *>(a.w_tensors[pc.tensor]) + pc.src_off, pc.len, a, acc);
+                                     static_cast<float *>(a.w_tensors[pc.tensor]) + pc.src_off, wh, pc.len, a, acc);
                     continue;
                 }
             }
-            if (dst) run<W, false, NT>(src + pc.dst_rel, dst, nullptr, nullptr, pc.len, a, acc);
+            if (dst) run<W, false, NT>(src + pc.dst_rel, dst, nullptr, nullptr, nullptr, pc.len, a, acc);
         }
     }
     const double s = gf_block_sum<NT>(l1);
@@ -250,6 +263,7 @@ extern "C" gf_status gf_unpack_sgd_update(const gf_plan *pl, const void *reduced
                                           float momentum, float learning_rate,
                                           float *w_pool, float *hu_pool,
                                           void *const *w_tensors, void *const *hu_tensors,
+                                          void *w_half_pool, void *const *w_half_tensors,
                                           float *out_pool, float *reduced_l1,
                                           void *workspace, gf_stream stream)
 {
@@ -258,12 +272,14 @@ extern "C" gf_status gf_unpack_sgd_update(const gf_plan *pl, const void *reduced
     const bool pool_form = w_pool && hu_pool && !w_tensors && !hu_tensors;
     const bool tensor_form = w_tensors && hu_tensors && !w_pool && !hu_pool;
     if (pool_form == tensor_form) return GF_EINVAL;
+    if ((pool_form && w_half_tensors) || (tensor_form && w_half_pool)) return GF_EINVAL;   // same form as w
     UnpackArgs a{};
     a.reduced = reduced;
     a.sel_idx = sel_idx;
     a.out_pool = out_pool;
     a.w_pool = w_pool; a.hu_pool = hu_pool;
     a.w_tensors = w_tensors; a.hu_tensors = hu_tensors;
+    a.wh_pool = static_cast<uint16_t *>(w_half_pool); a.wh_tensors = w_half_tensors;
     a.reduced_l1 = reduced_l1;
     a.alpha = alpha; a.momentum = momentum; a.lr = learning_rate;
     return unpack_common(pl, a, L, k, true, stream);

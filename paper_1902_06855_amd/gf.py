@@ -76,7 +76,7 @@ _ring_reduce_range = _sig("gf_ring_reduce_range", C.c_int, _vp, _vp, _i64, _vp, 
 _unpack_range = _sig("gf_unpack_range", C.c_int, _vp, _vp, _i64, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp)
 _unpack_apply = _sig("gf_unpack_apply", C.c_int, _vp, _vp, _i64, _vp, _i32, _f32, _vp, _vp, _vp, _vp, _vp)
 _unpack_sgd_update = _sig("gf_unpack_sgd_update", C.c_int, _vp, _vp, _i64, _vp, _i32, _f32, _f32, _f32, _vp, _vp, _vp,
-                          _vp, _vp, _vp, _vp, _vp)
+                          _vp, _vp, _vp, _vp, _vp, _vp, _vp)
 _csc_iteration = _sig("gf_csc_iteration", C.c_int, _vp, _u32, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _f32, _f32, _vp,
                       _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp)
 
@@ -264,11 +264,13 @@ def gf_unpack_apply(plan: Plan, reduced, L: int, *, sel_idx=None, k: int = 0, al
 
 def gf_unpack_sgd_update(plan: Plan, reduced, L: int, *, sel_idx=None, k: int = 0, alpha: float = 1.0,
                          momentum: float, learning_rate: float, w_pool=None, hu_pool=None, w_tensors=None,
-                         hu_tensors=None, out_pool=None, reduced_l1=None, workspace=None, stream=None) -> None:
+                         hu_tensors=None, w_half_pool=None, w_half_tensors=None, out_pool=None, reduced_l1=None,
+                         workspace=None, stream=None) -> None:
     _check(_unpack_sgd_update(plan.handle, _dptr(reduced), int(L), _dptr(sel_idx), int(k), float(alpha),
                               float(momentum), float(learning_rate), _dptr(w_pool), _dptr(hu_pool),
-                              _dptr(w_tensors), _dptr(hu_tensors), _dptr(out_pool), _dptr(reduced_l1),
-                              _dptr(workspace), _stream(stream)), "gf_unpack_sgd_update")
+                              _dptr(w_tensors), _dptr(hu_tensors), _dptr(w_half_pool), _dptr(w_half_tensors),
+                              _dptr(out_pool), _dptr(reduced_l1), _dptr(workspace), _stream(stream)),
+           "gf_unpack_sgd_update")
 
 
 def gf_csc_iteration(plan: Plan, modifiers: int = 0, *, grads=None, pools=None, residual, sel_idx, k: int,

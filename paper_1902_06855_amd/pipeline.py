@@ -31,7 +31,7 @@ class Pipeline:
                  k: int = 0, mu: float = 1.0, wire: str = "f16", schedule: str = "lagged",
                  scatter_out: bool = False, allgather: bool = False, device: str = "cuda",
                  sgd: Optional[tuple] = None, k_max: Optional[int] = None, grad: str = "f32",
-                 zero_copy: bool = False, groups: int = 0, fast: bool = True):
+                 zero_copy: bool = False, groups: int = 0, fast: bool = True, half_weights: bool = False):
         assert schedule in ("lagged", "immediate")
         # fast: the calls of an iteration hand the slot map and the unfinished chunk norms to each
         # other through the workspace (two small launches fewer per iteration; `self.l1` is then
@@ -96,6 +96,17 @@ class Pipeline:
                 self.w_tab, self.hu_tab = gf.ptr_table(self.w, device), gf.ptr_table(self.hu, device)
             else:
                 self.w, self.hu = new(self.N, torch.float32), new(self.N, torch.float32)
+        # half_weights: the update also maintains the FP16 copy of the weights that forward and
+        # backward use under mixed precision (Section 2.5), in the same form as the weights
+        self.w16 = self.w16_tab = None
+        if half_weights:
+            if sgd is None:
+                raise ValueError("half_weights belongs to the SGD-update step: pass sgd=(momentum, learning_rate)")
+            if scatter_out:
+                self.w16 = [new(s, torch.float16) for s in self.sizes]
+                self.w16_tab = gf.ptr_table(self.w16, device)
+            else:
+                self.w16 = new(self.N, torch.float16)
         self.grads_tab = self.pools_tab = None
         self._keep = None
         self.probe = None            # list to collect (stage, start event, end event) per launch
@@ -176,7 +187,9 @@ class Pipeline:
             gf.gf_unpack_sgd_update(self.plan, self.reduced, self.cap, sel_idx=self.sel if self.chunk else None,
                                     k=self.k, alpha=self.alpha, momentum=self.sgd[0], learning_rate=self.sgd[1],
                                     w_pool=self.w if pooled else None, hu_pool=self.hu if pooled else None,
-                                    w_tensors=self.w_tab, hu_tensors=self.hu_tab, out_pool=self.out_pool,
+                                    w_tensors=self.w_tab, hu_tensors=self.hu_tab,
+                                    w_half_pool=self.w16 if (pooled and self.w16 is not None) else None,
+                                    w_half_tensors=self.w16_tab, out_pool=self.out_pool,
                                     reduced_l1=self.red_l1 if self.chunk else None, workspace=self.ws)
             return
         if self.chunk:

@@ -237,6 +237,13 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert status(gf.gf_unpack_sgd_update, csc, fake, 1025, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake, **upd) == E
     assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake, **upd) == S
     assert status(gf.gf_unpack_sgd_update, dense, fake, 8192, w_tensors=fake, hu_tensors=fake, **upd) == S
+    # the FP16 copy of the weights comes in the same form as the weights
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake,
+                  w_half_tensors=fake, **upd) == E
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_tensors=fake, hu_tensors=fake,
+                  w_half_pool=fake, **upd) == E
+    assert status(gf.gf_unpack_sgd_update, csc, fake, 1024, sel_idx=fake, k=1, w_pool=fake, hu_pool=fake,
+                  w_half_pool=fake, **upd) == S
 
 
 def test_modifier_bits_and_range_calls_validate_before_touching_the_gpu():

@@ -45,6 +45,7 @@ def _draw(seed):
                mu=float(rng.choice([1.0, 1.0, 0.5])), density=float(rng.choice([0.05, 0.3, 0.3, 1.0])),
                allgather=bool(rng.integers(0, 2)), scatter=bool(rng.integers(0, 2)),
                sgd=bool(rng.integers(0, 3) == 0), odd_address=bool(rng.integers(0, 3) == 0),
+               half=bool(seed % 3 == 0),                          # with sgd: also the FP16 copy of the weights
                boost_last=bool(rng.integers(0, 2)),              # pushes the short last chunk into the selection
                warmup=int(rng.choice([0, 0, 3])) if (chunk and schedule == "lagged") else 0,
                fast=bool(seed % 2))
@@ -78,12 +79,18 @@ def test_random_configuration(gfm, seed):
     mom, lr = 0.9, -0.125
     pipe = pl.Pipeline(w.sizes, w.P, w.chunk, w.theta, w.loss_scale, k=ks[0], k_max=max(ks), mu=w.mu, wire=w.wire,
                        schedule=c["schedule"], grad=c["grad"], groups=c["groups"], fast=c["fast"],
-                       allgather=c["allgather"], scatter_out=c["scatter"], sgd=(mom, lr) if c["sgd"] else None)
+                       allgather=c["allgather"], scatter_out=c["scatter"], sgd=(mom, lr) if c["sgd"] else None,
+                       half_weights=c["sgd"] and c["half"])
     st = op.new_state(w.P, w.N)
     it, nt = (torch.int16, np.int16) if w.wire == "f16" else (torch.int32, np.int32)
     alpha = np.float32(1.0) / np.float32(w.loss_scale)
     w_ref = np.random.default_rng(seed).standard_normal(w.N).astype(np.float32)
     hu_ref = np.zeros(w.N, dtype=np.float32)
+    half = c["sgd"] and c["half"]
+    w16_ref = np.full(w.N, 0x3C00, dtype=np.uint16) if half else None       # ones, where never updated
+    if half:
+        for x in (pipe.w16 if c["scatter"] else [pipe.w16]):
+            x.fill_(1.0)
     if c["sgd"]:
         if c["scatter"]:
             for j, v in enumerate(op.views(w_ref, w.sizes)):
@@ -151,16 +158,23 @@ def test_random_configuration(gfm, seed):
                 same_bits(pipe.out_tensors[j], np.ascontiguousarray(v), f"{what} t={t} out tensor {j}")
         if c["sgd"]:
             if w.chunk:
-                ob.sgd_update(red, w.N, w.chunk, sel_used, alpha, mom, lr, w_ref, hu_ref, None, w.wire)
+                ob.sgd_update(red, w.N, w.chunk, sel_used, alpha, mom, lr, w_ref, hu_ref, None, w.wire, w_half=w16_ref)
             else:
-                ob.sgd_update(red, w.N, w.N, np.array([0], dtype=np.int32), alpha, mom, lr, w_ref, hu_ref, None, w.wire)
+                ob.sgd_update(red, w.N, w.N, np.array([0], dtype=np.int32), alpha, mom, lr, w_ref, hu_ref, None, w.wire,
+                              w_half=w16_ref)
             if c["scatter"]:
                 for j, (wv, hv) in enumerate(zip(op.views(w_ref, w.sizes), op.views(hu_ref, w.sizes))):
                     same_bits(pipe.w[j], np.ascontiguousarray(wv), f"{what} t={t} w tensor {j}")
                     same_bits(pipe.hu[j], np.ascontiguousarray(hv), f"{what} t={t} hu tensor {j}")
+                if half:
+                    for j, hv in enumerate(op.views(w16_ref, w.sizes)):
+                        same_bits(pipe.w16[j].view(torch.int16), np.ascontiguousarray(hv).view(np.int16),
+                                  f"{what} t={t} fp16 weights of tensor {j}")
             else:
                 same_bits(pipe.w, w_ref, f"{what} t={t} w")
                 same_bits(pipe.hu, hu_ref, f"{what} t={t} hu")
+                if half:
+                    same_bits(pipe.w16.view(torch.int16), w16_ref.view(np.int16), f"{what} t={t} fp16 weights")
 
 
 def test_the_draws_cover_what_they_are_meant_to():
@@ -168,6 +182,7 @@ def test_the_draws_cover_what_they_are_meant_to():
     cs = [_draw(s) for s in range(N_DRAWS)]
     assert {16, 32, 64} <= {c["P"] for c in cs}
     assert any(0 < c["chunk"] < 64 for c in cs) and any(c["chunk"] % 4 for c in cs if c["chunk"])
+    assert any(c["sgd"] and c["half"] and c["scatter"] for c in cs) and any(c["sgd"] and c["half"] and not c["scatter"] for c in cs)
     for key in ("allgather", "scatter", "sgd", "odd_address", "boost_last", "fast"):
         assert any(c[key] for c in cs) and any(not c[key] for c in cs), key
     assert any(c["warmup"] for c in cs) and any(c["sgd"] and c["chunk"] == 0 for c in cs)
