@@ -83,7 +83,7 @@ __device__ __forceinline__ void run(const W *src_, float *dst_, float *hu_, floa
         }
     };
 
-    constexpr int U = 4;
+    constexpr int U = UPD ? 4 : 8;
     int v = threadIdx.x;
     for (; v + (U - 1) * NT < nvec; v += U * NT) {
         W4 x[U];
