@@ -36,12 +36,12 @@ HBM_PEAK_GBS = 8000.0
 # read + bytes written between L2 and the fabric, from the tables under profiles/.  Keyed by
 # (workload, input layout, schedule): a run in any other configuration reports null.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/k_fuse_fused_resnet50_csc.md: FETCH 6 394 785.8 x 2 KiB + WRITE 6 423 586.2 KiB per launch
-    ("resnet50_csc", "gather", "lagged"): 13096521376 + 6577752224,
-    # profiles/k_fuse_fused_alexnet_csc.md: FETCH 3 813 234.1 x 2 KiB + WRITE 4 002 746.8 KiB per launch
-    ("alexnet_csc", "gather", "lagged"): 7809503424 + 4098812680,
-    # profiles/kernel_stats_other_workloads.md, cast kernel: FETCH 953 890.0 x 2 KiB + WRITE 952 581.8 KiB
-    ("alexnet_dense", "gather", "dense"): 1953566797 + 975443712,
+    # profiles/k_fuse_fused_resnet50_csc.md: FETCH 6 394 802.1 x 2 KiB + WRITE 6 423 586.2 KiB per launch
+    ("resnet50_csc", "gather", "lagged"): 13096554688 + 6577752272,
+    # profiles/k_fuse_fused_alexnet_csc.md: FETCH 3 813 246.4 x 2 KiB + WRITE 4 002 746.6 KiB per launch
+    ("alexnet_csc", "gather", "lagged"): 7809528704 + 4098812552,
+    # profiles/kernel_stats_other_workloads.md, cast kernel: FETCH 953 915.5 x 2 KiB + WRITE 952 581.8 KiB
+    ("alexnet_dense", "gather", "dense"): 1953619021 + 975443712,
 }
 
 DEFAULT_WORKLOAD = "resnet50_csc"     # the largest single-GPU configuration of the five
