@@ -130,7 +130,7 @@ def exchange_sum(contributions):
     return out
 
 
-def run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T, groups=0):
+def run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T, groups=0, ks=None):
     """grads[t][p][j]: tensor j (ID order) of worker p at iteration t.  Returns per iteration what
     every worker ended with."""
     P = len(grads[0])
@@ -140,6 +140,9 @@ def run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T, groups=0):
     sel = None
     log = []
     for t in range(T):
+        # ks: the number of important chunks per iteration (warm-up changes it); the chunks of
+        # iteration t + 1 are chosen at the end of iteration t, ks[t + 1] of them
+        k, k_after = (ks[t], ks[t + 1]) if ks else (k, k)
         for w in workers:
             w.accumulate(w.place(grads[t][w.rank], sizes))
         norms = [w.local_norms(C) for w in workers]
@@ -183,7 +186,7 @@ def run_cluster(grads, sizes, C, k, S, mu, theta, wire, schedule, T, groups=0):
         if schedule == "lagged":
             score = exchange_sum(shares)
             entry["score_post"] = score
-            sel = top_k(score, k)
+            sel = top_k(score, k_after)
             entry["sel_next"] = list(sel)
         log.append(entry)
     return log
@@ -281,6 +284,29 @@ def test_checker_dense_iteration_equals_the_cluster_simulation(theta, wire):
         assert np.ascontiguousarray(r["send"][p]).tobytes() == bits(sent[p], wt)
     assert np.ascontiguousarray(r["reduced"]).tobytes() == bits(workers[0].buf, wt)
     assert r["out"].tobytes() == bits(want_out, np.float32)
+
+
+def test_checker_iterations_through_a_warm_up_ramp():
+    """Warm-up dense training (Section 3.2): the sparsity ratio ramps linearly from zero, so the
+    number of important chunks shrinks from all of them; the count of iteration t + 1 is what the
+    selection at the end of iteration t takes."""
+    from oracle import binding as ob
+    rng = np.random.default_rng(11)
+    P, sizes, C, S, T = 3, [30, 50, 21], 5, 32.0, 6
+    nc = -(-sum(sizes) // C)
+    ks = [ob.warmup_k(nc, 0.2, t, 4) for t in range(T + 1)]
+    assert ks[0] == nc and ks[4] == ks[5] == -(-nc // 5) and sorted(ks, reverse=True) == ks     # dense first, then the ramp
+    grads = [[[rng.standard_normal(n).astype(np.float32) for n in sizes] for _ in range(P)] for _ in range(T)]
+    log = run_cluster(grads, sizes, C, None, S, 1.0, 12, "f16", "lagged", T, ks=ks)
+    st = op.new_state(P, sum(sizes))
+    for t in range(T):
+        pools = np.stack([op.fuse(grads[t][p], sizes) for p in range(P)])
+        r = op.csc_iteration(st, pools, C, ks[t], S, 1.0, "lagged", "f16", k_next=ks[t + 1], theta=12)
+        assert list(r["sel"]) == log[t]["sel"] and len(r["sel"]) == ks[t], f"t={t}"
+        assert list(r["sel_next"]) == log[t]["sel_next"] and len(r["sel_next"]) == ks[t + 1], f"t={t}"
+        assert np.ascontiguousarray(r["reduced"]).tobytes() == bits(log[t]["reduced"], np.float16), f"t={t}"
+        for p in range(P):
+            assert st.hg[p].tobytes() == bits(log[t]["hg"][p], np.float32), f"t={t}"
 
 
 def test_the_simulation_itself_sums_what_it_should():
