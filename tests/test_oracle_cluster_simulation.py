@@ -320,3 +320,34 @@ def test_the_simulation_itself_sums_what_it_should():
     for w in workers:
         assert [float(v) for v in w.buf[3:]] == [float(10 * (i % 7)) for i in range(3, n)]
         assert [float(v) for v in w.buf[:3]] == [float((w.rank + 1) * i) for i in range(3)]
+
+
+def test_every_worker_applies_the_same_update():
+    """Algorithm 1's SGD-update step inside the job: every worker updates its own copy of the
+    weights from the chunks it received; the copies stay identical (they all hold the same reduced
+    values) and equal the checker's, whose update runs once."""
+    from oracle import binding as ob
+    rng = np.random.default_rng(21)
+    P, sizes, C, k, S, T = 3, [17, 40, 9], 6, 4, 16.0, 5
+    N = sum(sizes)
+    momentum, lr = f32(0.9), f32(-0.1)
+    alpha = f32(1.0) / f32(S)
+    grads = [[[rng.standard_normal(n).astype(np.float32) for n in sizes] for _ in range(P)] for _ in range(T)]
+    log = run_cluster(grads, sizes, C, k, S, 1.0, 1 << 60, "f16", "lagged", T)
+    w0 = rng.standard_normal(N).astype(np.float32)
+    copies = [dict(w=[f32(v) for v in w0], hu=[f32(0.0)] * N) for _ in range(P)]
+    w_ref, hu_ref = w0.copy(), np.zeros(N, dtype=np.float32)
+    for t in range(T):
+        red = np.array(log[t]["reduced"], dtype=np.float16)
+        for cp in copies:                                     # what each worker does on its own
+            for j, c in enumerate(log[t]["sel"]):
+                for i in range(min(N, (c + 1) * C) - c * C):
+                    g = f32(f32(red[j * C + i]) * alpha)
+                    e = c * C + i
+                    cp["hu"][e] = f32(f32(momentum * cp["hu"][e]) + f32(lr * g))
+                    cp["w"][e] = f32(cp["w"][e] + cp["hu"][e])
+        ob.sgd_update(red.view(np.uint16), N, C, np.array(log[t]["sel"], dtype=np.int32), alpha, momentum, lr,
+                      w_ref, hu_ref)
+        for cp in copies:
+            assert bits(cp["w"], np.float32) == w_ref.tobytes() and bits(cp["hu"], np.float32) == hu_ref.tobytes(), f"t={t}"
+    assert not np.array_equal(w_ref, w0)
