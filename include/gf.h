@@ -13,7 +13,8 @@
  *     pointers are ordinary host memory.  Pointer *tables* (arrays of
  *     pointers) passed to the compute calls are themselves device arrays.
  *   - The library owns only the plan (host tables + a few KB of device
- *     tables).  Compute calls allocate nothing, never synchronise with the
+ *     tables) and the fixed scratch array of gf_fuse_pack_static, which is part
+ *     of its code object.  Compute calls allocate nothing, never synchronise with the
  *     host, and are enqueued on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream).
  *   - Data pointers need only their natural alignment (4 bytes for fp32,
