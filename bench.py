@@ -15,7 +15,11 @@ iteration boundary on the launch stream; `roofline` describes the dominant
 kernel, bracketed by events on the launch stream inside the timed region;
 `config.stages` gives every stage's time and GB/s from a second, untimed pass
 with every stage bracketed; `cpu_baseline` is the CPU checker run on the host
-cores on a bounded sample of the same workload.
+cores on a bounded sample of the same workload.  `config.others` holds the
+other configurations, one-worker rows (the shape one GPU of a real job runs),
+the same iterations replayed as HIP graphs (`+graph`), issued by one host call
+each (`+one_call`, gf_csc_iteration) and with Algorithm 1's update step fused
+into the unpack (`+sgd_update`); `--ladder` adds the lower rungs of Tables 1-2.
 """
 from __future__ import annotations
 
